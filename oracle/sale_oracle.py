@@ -1,0 +1,276 @@
+"""CPU oracle for SALE's prefill attention path (arXiv 2505.24179).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition of what
+the GPU library must compute.  Only the test-suite, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it; no product code path does.
+It shares nothing with the HIP sources (no tables, no helpers, no packing
+code) and never imports the GPU binding.
+
+Everything is numpy.  Floating point is fp64 except where the method itself
+fixes a precision: the 4-bit quantizer works in fp32 (the codes are integer
+decisions, and both sides must take them in the same precision).
+
+Notation follows the paper: Q, K, V are N x d per head, b_q / b_k the block
+sizes, N_q = N / b_q, N_k = N / b_k, M_bs the block mask, S the attention
+weights, m~ / l~ the sink-local statistics, tau the threshold.
+
+Pins (tests/test_oracle_*.py): quantizer invariants and the lossless grid;
+integer products against pure-Python brute force; the hand-derived 4x4-block
+toy; the lossless-grid case of the mask against a library logsumexp; Eq. 3
+against Eq. 4; structural invariants of the mask; attention with every block
+selected against brute-force causal softmax; the renormalisation identity for
+dropped blocks.  No function here is "parity unpinned".
+"""
+
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+QMAX = 7  # symmetric signed 4-bit codes in [-7, 7]; -8 is never produced
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2 "4-bit attention weight approximation": quantization of Q and K
+# --------------------------------------------------------------------------
+def quantize_blocks(x: np.ndarray, block: int):
+    """Per-block symmetric 4-bit quantization (Sec. 3.2; Alg. 1 inputs Q~, K~).
+
+    x      : float32 [H, N, d], values exactly representable in bf16.
+    block  : rows per block (b_q for Q, b_k for K); one fp32 scale per
+             (head, block) shared by all block*d elements.
+    returns: codes int8 [H, N, d] in [-7, 7], scales float32 [H, N/block].
+
+    All arithmetic is IEEE fp32, one operation at a time:
+      amax = max|x|;  scale = amax / 7;  inv = 7 / amax;
+      code = clamp(round_half_even(x * inv), -7, 7).
+    A block of zeros gets scale 1 and codes 0.
+    """
+    x = np.asarray(x, dtype=np.float32)
+    H, N, d = x.shape
+    assert N % block == 0
+    nb = N // block
+    xb = x.reshape(H, nb, block * d)
+    amax = np.max(np.abs(xb), axis=2).astype(np.float32)            # [H, nb]
+    zero = amax == np.float32(0.0)
+    safe = np.where(zero, np.float32(1.0), amax).astype(np.float32)
+    seven = np.float32(QMAX)
+    scale = np.where(zero, np.float32(1.0), safe / seven).astype(np.float32)
+    inv = np.where(zero, np.float32(0.0), seven / safe).astype(np.float32)
+    y = (xb * inv[:, :, None]).astype(np.float32)                    # one fp32 multiply
+    code = np.rint(y)                                                # ties to even
+    code = np.clip(code, -QMAX, QMAX).astype(np.int8)
+    return code.reshape(H, N, d), scale
+
+
+def pack_int4(codes: np.ndarray) -> np.ndarray:
+    """Nibble packing of the boundary format: byte c of a row holds channel 2c
+    in bits 0..3 and channel 2c+1 in bits 4..7, each 4-bit two's complement."""
+    c = np.asarray(codes).astype(np.int16)
+    lo = c[..., 0::2] & 0xF
+    hi = c[..., 1::2] & 0xF
+    return (lo | (hi << 4)).astype(np.uint8)
+
+
+def unpack_int4(packed: np.ndarray) -> np.ndarray:
+    p = np.asarray(packed, dtype=np.uint8).astype(np.int16)
+    lo = p & 0xF
+    hi = (p >> 4) & 0xF
+    lo = np.where(lo >= 8, lo - 16, lo)
+    hi = np.where(hi >= 8, hi - 16, hi)
+    out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.int8)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    return out
+
+
+def int_products(q_codes: np.ndarray, k_codes: np.ndarray) -> np.ndarray:
+    """A[r, c] = sum_k Q~[r, k] * K~[c, k]  (Alg. 1, the product inside
+    Dequantize).  Exact: every partial sum is an integer below 2^53, so the
+    fp64 library matmul used as the step is exact; returned as int32."""
+    a = np.asarray(q_codes, dtype=np.float64) @ np.asarray(k_codes, dtype=np.float64).T
+    return a.astype(np.int32)
+
+
+def dequantize(a_int: np.ndarray, s_q: float, s_k, d: int) -> np.ndarray:
+    """S~ = A * s_q * s_k / sqrt(d)  (Alg. 1, approximate attention weight)."""
+    return np.asarray(a_int, dtype=np.float64) * float(s_q) * np.asarray(s_k, dtype=np.float64) / math.sqrt(d)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2 "Relative importance estimation" and Alg. 1
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class Geometry:
+    """Block geometry (Sec. 3.1; Alg. 1 inputs)."""
+    seq_len: int
+    head_dim: int
+    block_q: int = 64
+    block_k: int = 64
+    sink_blocks: int = 1
+    local_blocks: int = 4
+    stats_causal: bool = False   # False: the statistics ignore the causal mask (Alg. 1 comment)
+
+    @property
+    def n_q(self) -> int:
+        return self.seq_len // self.block_q
+
+    @property
+    def n_k(self) -> int:
+        return self.seq_len // self.block_k
+
+    def j_last(self, i: int) -> int:
+        """Last key block any row of query block i may attend causally."""
+        return ((i + 1) * self.block_q - 1) // self.block_k
+
+    def sink_local(self, i: int) -> list:
+        """I_SL of Alg. 1 in key-block units: the sink blocks and the
+        local_blocks blocks ending at (and including) the diagonal one."""
+        jl = self.j_last(i)
+        s = set(range(min(self.sink_blocks, jl + 1)))
+        s |= set(range(max(0, jl - self.local_blocks + 1), jl + 1))
+        return sorted(s)
+
+
+def sink_local_stats(geo: Geometry, i: int, q_blk: np.ndarray, k: np.ndarray):
+    """m~_r = max S[r, c], l~_r = sum exp(S[r, c] - m~_r) over the key tokens c
+    of the sink-local blocks of query block i (display equation of Sec. 3.2),
+    S from the unquantized inputs, in fp64.  q_blk: [b_q, d], k: [N, d]."""
+    q = np.asarray(q_blk, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    cols = np.concatenate([np.arange(j * geo.block_k, (j + 1) * geo.block_k) for j in geo.sink_local(i)])
+    s = (q @ kk[cols].T) / math.sqrt(geo.head_dim)                   # [b_q, |I_SL| * b_k]
+    if geo.stats_causal:
+        rows = i * geo.block_q + np.arange(geo.block_q)
+        s = np.where(cols[None, :] <= rows[:, None], s, -np.inf)
+    m = s.max(axis=1)
+    l = np.exp(s - m[:, None]).sum(axis=1)
+    return m, l
+
+
+def select_row(geo: Geometry, i: int, q_blk, k, q_codes_blk, k_codes, s_q_i: float, s_k, tau: float):
+    """One query block of Alg. 1: returns (mask_row bool [N_k], margin float64
+    [N_k], margin_thr float64 [N_k], thr float64 [b_q], m~, l~).
+
+    mask_row[j] = 1 for j in I_SL; for a middle block j (0 <= j <= j_last, not
+    in I_SL) it is 1 iff some row r has max_c S~[r, c] >= ln(tau * l~_r) + m~_r,
+    the log form of "max P~ >= tau" (Eq. 3, Eq. 4 with the parenthesis where
+    Eq. 3 puts it); blocks past j_last are 0.  margin[j] = max_r (rowmax S~ -
+    thr_r) for middle blocks (nan elsewhere) and margin_thr[j] the thr_r of the
+    row attaining it: the caller uses them to find decisions that sit on the
+    threshold.
+    """
+    m, l = sink_local_stats(geo, i, q_blk, k)
+    thr = np.log(tau * l) + m
+    jl = geo.j_last(i)
+    isl = set(geo.sink_local(i))
+    mask = np.zeros(geo.n_k, dtype=bool)
+    margin = np.full(geo.n_k, np.nan)
+    margin_thr = np.full(geo.n_k, np.nan)
+    for j in isl:
+        mask[j] = True
+    middle = [j for j in range(jl + 1) if j not in isl]
+    if middle:
+        bk = geo.block_k
+        a = int_products(q_codes_blk, k_codes[: (jl + 1) * bk])      # [b_q, (jl+1) b_k]
+        for j in middle:
+            s_tilde = dequantize(a[:, j * bk:(j + 1) * bk], s_q_i, s_k[j], geo.head_dim)
+            row_max = s_tilde.max(axis=1)
+            r_star = int(np.argmax(row_max - thr))
+            margin[j] = row_max[r_star] - thr[r_star]
+            margin_thr[j] = thr[r_star]
+            mask[j] = bool(np.any(row_max >= thr))
+    return mask, margin, margin_thr, thr, m, l
+
+
+def select_head(geo: Geometry, q, k, q_codes, k_codes, s_q, s_k, tau: float):
+    """Alg. 1 for one (query head, its KV head): M_bs bool [N_q, N_k] plus the
+    margins and statistics of every query block."""
+    bq = geo.block_q
+    mask = np.zeros((geo.n_q, geo.n_k), dtype=bool)
+    margin = np.full((geo.n_q, geo.n_k), np.nan)
+    margin_thr = np.full((geo.n_q, geo.n_k), np.nan)
+    thr = np.zeros(geo.seq_len)
+    m = np.zeros(geo.seq_len)
+    l = np.zeros(geo.seq_len)
+    for i in range(geo.n_q):
+        rs = slice(i * bq, (i + 1) * bq)
+        mask[i], margin[i], margin_thr[i], thr[rs], m[rs], l[rs] = select_row(
+            geo, i, q[rs], k, q_codes[rs], k_codes, float(s_q[i]), s_k, tau)
+    return mask, margin, margin_thr, thr, m, l
+
+
+def relative_attention_score(s_tilde, m, l):
+    """Eq. 3: P~[r, c] = exp(S~[r, c] - m~_r) / l~_r."""
+    return np.exp(np.asarray(s_tilde, dtype=np.float64) - np.asarray(m)[:, None]) / np.asarray(l)[:, None]
+
+
+def pack_mask_words(mask_row: np.ndarray) -> np.ndarray:
+    """Boundary layout of one mask row: bit (j mod 64) of word j // 64."""
+    n_k = mask_row.shape[-1]
+    words = np.zeros((n_k + 63) // 64, dtype=np.uint64)
+    for j in np.nonzero(mask_row)[0]:
+        words[j // 64] |= np.uint64(1) << np.uint64(j % 64)
+    return words
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1: masked attention (Eq. 1 with the block mask of Eq. 2)
+# --------------------------------------------------------------------------
+def attention_probs_block(geo: Geometry, i: int, q_blk, k, mask_row):
+    """P = Softmax(S + M) for the rows of query block i; M = M_c + M_s with
+    M_s from the block mask row (Eq. 1, Eq. 2).  Returns [b_q, N] fp64."""
+    q = np.asarray(q_blk, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    n = kk.shape[0]
+    s = (q @ kk.T) / math.sqrt(geo.head_dim)
+    rows = i * geo.block_q + np.arange(geo.block_q)
+    cols = np.arange(n)
+    allowed = (cols[None, :] <= rows[:, None]) & np.repeat(np.asarray(mask_row, dtype=bool), geo.block_k)[None, :]
+    s = np.where(allowed, s, -np.inf)
+    mx = s.max(axis=1, keepdims=True)
+    e = np.exp(s - mx)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def attention_block(geo: Geometry, i: int, q_blk, k, v, mask_row):
+    """O rows of query block i (Eq. 1): returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    q = np.asarray(q_blk, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    n = kk.shape[0]
+    s = (q @ kk.T) / math.sqrt(geo.head_dim)
+    rows = i * geo.block_q + np.arange(geo.block_q)
+    cols = np.arange(n)
+    allowed = (cols[None, :] <= rows[:, None]) & np.repeat(np.asarray(mask_row, dtype=bool), geo.block_k)[None, :]
+    s = np.where(allowed, s, -np.inf)
+    mx = s.max(axis=1, keepdims=True)
+    e = np.exp(s - mx)
+    den = e.sum(axis=1, keepdims=True)
+    o = (e / den) @ np.asarray(v, dtype=np.float64)
+    return o, (mx + np.log(den))[:, 0]
+
+
+def attention_head(geo: Geometry, q, k, v, mask):
+    """Eq. 1 for one head with block mask M_bs [N_q, N_k]; O fp64 [N, d]."""
+    bq = geo.block_q
+    o = np.zeros((geo.seq_len, np.asarray(v).shape[1]))
+    lse = np.zeros(geo.seq_len)
+    for i in range(geo.n_q):
+        rs = slice(i * bq, (i + 1) * bq)
+        o[rs], lse[rs] = attention_block(geo, i, q[rs], k, v, mask[i])
+    return o, lse
+
+
+def dense_mask(geo: Geometry) -> np.ndarray:
+    """Every causally visible block selected."""
+    mask = np.zeros((geo.n_q, geo.n_k), dtype=bool)
+    for i in range(geo.n_q):
+        mask[i, : geo.j_last(i) + 1] = True
+    return mask
+
+
+def is_borderline(margin, thr_scale, rel: float = 1e-5):
+    """Decisions whose margin lies within rel * max(1, |thr|) of zero."""
+    return np.abs(margin) <= rel * np.maximum(1.0, np.abs(thr_scale))
