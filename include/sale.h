@@ -1,0 +1,169 @@
+/*
+ * sale.h - C ABI of the MI355X (gfx950) implementation of SALE's prefill
+ * attention path (arXiv 2505.24179):
+ *
+ *   quantize Q,K to 4 bit  ->  Selection-Pass (block mask)  ->  Computation-Pass
+ *   (block-sparse causal attention), plus a dense causal kernel of the same
+ *   design used as the speed-up denominator.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ * - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *   never allocates or frees memory.  Scratch comes from a caller-provided
+ *   workspace whose size sale_workspace_bytes() reports.
+ * - Calls are asynchronous on the given hipStream_t (passed as void*; NULL =
+ *   the default stream), never synchronise and keep no global state.
+ * - All tensors are contiguous, row-major, last dimension fastest:
+ *     Q, O : bf16 [batch][n_q_heads ][seq_len][head_dim]
+ *     K, V : bf16 [batch][n_kv_heads][seq_len][head_dim]
+ *   Query head h reads KV head h / (n_q_heads / n_kv_heads)  (GQA).
+ * - Return value: SALE_OK (0) or a negative sale_status.  Arguments are checked
+ *   before anything is launched; a failed check launches nothing.
+ * - Supported geometry: head_dim = 128; block_q = block_k = 64; seq_len a
+ *   multiple of 64; n_q_heads a multiple of n_kv_heads.  (sale_quantize_qk
+ *   alone also accepts block sizes of 32.)  Anything else returns
+ *   SALE_ERR_UNSUPPORTED.
+ *
+ * Notation follows the paper: N = seq_len, d = head_dim, b_q / b_k block sizes,
+ * N_q = N / b_q, N_k = N / b_k, M_bs the block-level sparse mask (Sec. 3.1),
+ * m~ / l~ the sink-local statistics and tau the threshold (Sec. 3.2).
+ */
+#ifndef SALE_H_
+#define SALE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sale_status {
+  SALE_OK = 0,
+  SALE_ERR_NULL_ARG = -1,     /* a required pointer is NULL                       */
+  SALE_ERR_BAD_SHAPE = -2,    /* non-positive size, N not a multiple of the block */
+  SALE_ERR_UNSUPPORTED = -3,  /* valid but not implemented geometry / flag        */
+  SALE_ERR_WORKSPACE = -4,    /* workspace NULL or smaller than required          */
+  SALE_ERR_HIP = -5           /* a HIP runtime call or kernel launch failed       */
+} sale_status;
+
+/* The sink-local statistics see only keys at or before each query row.  Default
+ * (flag clear) follows Alg. 1's comment: the statistics ignore the causal mask
+ * inside the sink-local blocks. */
+#define SALE_FLAG_STATS_CAUSAL 1u
+
+typedef struct sale_params {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t seq_len;      /* N                                                     */
+  int32_t head_dim;     /* d, must be 128                                        */
+  int32_t block_q;      /* b_q                                                   */
+  int32_t block_k;      /* b_k                                                   */
+  int32_t sink_blocks;  /* key blocks at the start of every row that are always
+                           kept and feed the statistics (Alg. 1: block 0)        */
+  int32_t local_blocks; /* key blocks ending at, and including, the diagonal one
+                           that are always kept and feed the statistics          */
+  uint32_t flags;       /* SALE_FLAG_*                                           */
+} sale_params_t;
+
+/* Which call a workspace is for. */
+#define SALE_WS_SELECT 1
+#define SALE_WS_SPARSE_ATTN 2
+
+/* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
+ * parameters are invalid). */
+size_t sale_workspace_bytes(const sale_params_t* p, int which_call);
+
+/* Static description of a status code. */
+const char* sale_status_string(int status);
+
+/*
+ * Quantization stage (Sec. 3.2 "4-bit attention weight approximation"; inputs
+ * Q~, K~ of Alg. 1).  For every block of block_q rows of one Q head (block_k
+ * rows of one K head), over all rows*d elements x of the block, in IEEE fp32:
+ *   amax = max|x|; scale = amax / 7; code = clamp(rint(x * (7 / amax)), -7, 7)
+ * (round half to even; an all-zero block gets scale 1 and codes 0).
+ *
+ *   q, k     in : bf16, layouts above
+ *   q4       out: uint8 [batch][n_q_heads ][N][d/2]; byte c of a row holds channel
+ *                 2c in bits 0..3 and channel 2c+1 in bits 4..7 (two's complement)
+ *   k4       out: uint8 [batch][n_kv_heads][N][d/2], same packing
+ *   q_scale  out: fp32 [batch][n_q_heads ][N / block_q]
+ *   k_scale  out: fp32 [batch][n_kv_heads][N / block_k]
+ */
+int sale_quantize_qk(const sale_params_t* p, const void* q, const void* k,
+                     uint8_t* q4, uint8_t* k4, float* q_scale, float* k_scale,
+                     void* stream);
+
+/*
+ * Selection-Pass (Alg. 1; Eq. 3; Eq. 4; Sec. 3.4 "Reduction in dequantization
+ * operations").  For every query head and query block i:
+ *   1. I_SL(i) = the first sink_blocks key blocks and the local_blocks key
+ *      blocks ending at the diagonal block; those bits are set to 1 and the
+ *      statistics m~_r = max S[r,c], l~_r = sum exp(S[r,c] - m~_r) over their
+ *      key tokens are taken from the unquantized Q, K (S = Q K^T / sqrt(d)).
+ *   2. every other causally visible key block j is kept iff some row r has
+ *      max_c  A[r,c] * q_scale[i] * k_scale[j] / sqrt(d)  >=  ln(tau * l~_r) + m~_r,
+ *      A = Q~_i K~_j^T in exact integer arithmetic (the log form of
+ *      "max relative attention score >= tau").
+ *   3. key blocks past the diagonal are 0.
+ *
+ *   tau         in : fp32, DEVICE pointer, tau_len = 1 (shared) or n_q_heads
+ *   block_mask  out: uint64 [batch][n_q_heads][N_q][ceil(N_k/64)]; bit (j mod 64)
+ *                    of word j/64 is M_bs[i][j]
+ *   row_counts  out: int32 [batch][n_q_heads][N_q], number of kept blocks per row
+ *   m_out,l_out out: optional (may be NULL) fp32 [batch][n_q_heads][N]: m~, l~
+ *   ws             : workspace of sale_workspace_bytes(p, SALE_WS_SELECT) bytes
+ */
+int sale_select(const sale_params_t* p, const void* q, const void* k,
+                const uint8_t* q4, const uint8_t* k4,
+                const float* q_scale, const float* k_scale,
+                const float* tau, int32_t tau_len,
+                uint64_t* block_mask, int32_t* row_counts,
+                float* m_out, float* l_out,
+                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Computation-Pass (Sec. 3.1, Eq. 1 with the block mask of Eq. 2):
+ *   O = Softmax(Q K^T / sqrt(d) + M_c + M_s) V, computed only on the key blocks
+ * whose bit is set in block_mask (bf16 operands, fp32 accumulation and softmax).
+ * A query block whose diagonal bit is clear would leave rows without any key;
+ * the Selection-Pass never produces that, and for such rows O is 0 and lse -inf.
+ *
+ *   block_mask in : layout of sale_select
+ *   row_counts in : optional (may be NULL) per-row kept-block counts, used only
+ *                   to order work
+ *   o          out: bf16, layout of Q
+ *   lse        out: optional (may be NULL) fp32 [batch][n_q_heads][N], natural-log
+ *                   sum-exp of the kept logits of each row
+ *   ws            : workspace of sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN) bytes
+ *                   (may be NULL when that size is 0)
+ */
+int sale_sparse_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
+                     const uint64_t* block_mask, const int32_t* row_counts,
+                     void* o, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dense causal attention (Eq. 1 with M = M_c): the same kernel with every
+ * causally visible block kept.  The denominator of every reported speed-up.
+ */
+int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
+                    void* o, float* lse, void* stream);
+
+/*
+ * Parity hook: the exact integer products of the Selection-Pass,
+ *   out[r][c] = sum_t Q~[q_block*b_q + r][t] * K~[k_block_begin*b_k + c][t]
+ * for one (batch*head) index `q_head` (flattened batch*n_q_heads), computed
+ * with the same matrix instructions and operand handling the Selection-Pass
+ * uses.  out: int32 [b_q][(k_block_end - k_block_begin) * b_k].
+ */
+int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, const uint8_t* k4,
+                          int32_t q_head, int32_t q_block,
+                          int32_t k_block_begin, int32_t k_block_end,
+                          int32_t* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SALE_H_ */

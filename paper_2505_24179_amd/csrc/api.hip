@@ -1,0 +1,68 @@
+// Argument validation, geometry and the small query entry points of the C ABI.
+#include "sale_common.h"
+
+namespace sale {
+
+int validate_common(const sale_params_t* p, bool need_64x64) {
+  if (p->batch <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->seq_len <= 0) return SALE_ERR_BAD_SHAPE;
+  if (p->block_q <= 0 || p->block_k <= 0) return SALE_ERR_BAD_SHAPE;
+  if (p->seq_len % p->block_q != 0 || p->seq_len % p->block_k != 0) return SALE_ERR_BAD_SHAPE;
+  if (p->n_q_heads % p->n_kv_heads != 0) return SALE_ERR_BAD_SHAPE;
+  if (p->sink_blocks < 0 || p->local_blocks < 1) return SALE_ERR_BAD_SHAPE;
+  if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
+  if (p->flags & ~SALE_FLAG_STATS_CAUSAL) return SALE_ERR_UNSUPPORTED;
+  if (need_64x64) {
+    if (p->block_q != kBlockQ || p->block_k != kBlockK) return SALE_ERR_UNSUPPORTED;
+    if (p->seq_len > kMaxSeqLen) return SALE_ERR_UNSUPPORTED;
+  } else {
+    if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
+  }
+  // 32-bit index guards used by the kernels
+  if ((long)p->batch * p->n_q_heads * (long)(p->seq_len / 32) > 0x7FFFFFFFL) return SALE_ERR_UNSUPPORTED;
+  return SALE_OK;
+}
+
+Geo make_geo(const sale_params_t* p) {
+  Geo g;
+  g.n_qh = p->batch * p->n_q_heads;
+  g.n_kvh = p->batch * p->n_kv_heads;
+  g.hq_per_b = p->n_q_heads;
+  g.group = p->n_q_heads / p->n_kv_heads;
+  g.seq = p->seq_len;
+  g.n_qb = p->seq_len / kBlockQ;
+  g.n_kb = p->seq_len / kBlockK;
+  g.words = (g.n_kb + 63) / 64;
+  g.sink_blocks = p->sink_blocks;
+  g.local_blocks = p->local_blocks;
+  g.stats_causal = (p->flags & SALE_FLAG_STATS_CAUSAL) ? 1 : 0;
+  return g;
+}
+
+}  // namespace sale
+
+using namespace sale;
+
+extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
+  if (!p || validate_common(p, true) != SALE_OK) return 0;
+  const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
+  switch (which_call) {
+    case SALE_WS_SELECT:
+      return rows * sizeof(float);        // thr_r = ln(tau l~_r) + m~_r per query row
+    case SALE_WS_SPARSE_ATTN:
+      return 0;
+    default:
+      return 0;
+  }
+}
+
+extern "C" const char* sale_status_string(int status) {
+  switch (status) {
+    case SALE_OK: return "ok";
+    case SALE_ERR_NULL_ARG: return "a required pointer argument is NULL";
+    case SALE_ERR_BAD_SHAPE: return "invalid shape (non-positive size, or seq_len / heads not divisible)";
+    case SALE_ERR_UNSUPPORTED: return "geometry or flag not supported by this build";
+    case SALE_ERR_WORKSPACE: return "workspace missing or too small";
+    case SALE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}

@@ -1,0 +1,84 @@
+// Shared device-side types and small helpers for the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sale.h"
+
+namespace sale {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr int kHeadDim = 128;   // d
+constexpr int kBlockQ = 64;     // b_q
+constexpr int kBlockK = 64;     // b_k
+constexpr int kMaskWordsMax = 64;            // mask words per row the attention kernel stages in LDS
+constexpr int kMaxSeqLen = kMaskWordsMax * 64 * kBlockK;   // 262144 tokens
+
+// Flattened geometry handed to kernels.
+struct Geo {
+  int n_qh;        // batch * n_q_heads
+  int n_kvh;       // batch * n_kv_heads
+  int hq_per_b;    // n_q_heads (to index tau)
+  int group;       // n_q_heads / n_kv_heads
+  int seq;         // N
+  int n_qb;        // N / 64
+  int n_kb;        // N / 64
+  int words;       // ceil(n_kb / 64)
+  int sink_blocks;
+  int local_blocks;
+  int stats_causal;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __builtin_bit_cast(float, (unsigned)b << 16);
+}
+
+// Accumulator register r of lane `lane` in a 32x32 MFMA tile holds row
+// 8*(r/4) + 4*(lane/32) + r%4 of column lane%32.
+__device__ __forceinline__ int mfma32_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// Value held by the other half of the wave (lane ^ 32).
+__device__ __forceinline__ float swap_half(float x) { return __shfl_xor(x, 32, 64); }
+
+// Unit = (flattened query head, 64-row query block): the work of one wave.
+// Units of one KV head are numbered block-major, head-in-group minor, so the
+// four waves of a workgroup share their K (and V) rows.  Workgroups are dealt
+// round-robin over KV heads (one KV head per XCD / L2 when there are 8) and
+// longest rows first.
+struct Unit {
+  int kvh;     // flattened batch * kv head
+  int qh;      // flattened batch * q head
+  int i;       // query block
+  bool valid;  // false for the padding waves of the last workgroup
+};
+
+__device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
+  const int units = g.n_qb * g.group;
+  const int tiles = (units + 3) / 4;
+  Unit u;
+  u.kvh = block % g.n_kvh;
+  const int t = tiles - 1 - block / g.n_kvh;
+  const int id = t * 4 + wave;
+  u.valid = id < units;
+  u.i = u.valid ? id / g.group : 0;
+  u.qh = u.kvh * g.group + (u.valid ? id % g.group : 0);
+  return u;
+}
+
+int validate_common(const sale_params_t* p, bool need_64x64);
+Geo make_geo(const sale_params_t* p);
+
+}  // namespace sale

@@ -1,0 +1,175 @@
+"""Thin ctypes binding over libsale.so (the C ABI declared in include/sale.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch supplies device memory and the current stream.  Importing this
+module fails loudly when the built library is missing; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsale.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python -m paper_2505_24179_amd.build` "
+        "(there is no CPU or PyTorch fallback for the SALE kernels)")
+_lib = ctypes.CDLL(_LIB_PATH)
+
+OK = 0
+FLAG_STATS_CAUSAL = 1
+WS_SELECT = 1
+WS_SPARSE_ATTN = 2
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "seq_len", "head_dim",
+        "block_q", "block_k", "sink_blocks", "local_blocks")] + [("flags", ctypes.c_uint32)]
+
+
+@dataclass(frozen=True)
+class Params:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    seq_len: int
+    head_dim: int = 128
+    block_q: int = 64
+    block_k: int = 64
+    sink_blocks: int = 1
+    local_blocks: int = 4
+    flags: int = 0
+
+    def c(self) -> _Params:
+        return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.seq_len, self.head_dim,
+                       self.block_q, self.block_k, self.sink_blocks, self.local_blocks, self.flags)
+
+    @property
+    def n_q(self) -> int:
+        return self.seq_len // self.block_q
+
+    @property
+    def n_k(self) -> int:
+        return self.seq_len // self.block_k
+
+    @property
+    def words(self) -> int:
+        return (self.n_k + 63) // 64
+
+
+_vp, _sz, _i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+_pp = ctypes.POINTER(_Params)
+_SIGS = {
+    "sale_workspace_bytes": (_sz, [_pp, ctypes.c_int]),
+    "sale_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "sale_quantize_qk": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sale_select": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sale_sparse_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+EXPORTED = tuple(_SIGS)
+
+
+class SaleError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libsale status {status}: {_lib.sale_status_string(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise SaleError(status)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def raw():
+    """The ctypes library handle (tests of error paths call entry points directly)."""
+    return _lib
+
+
+def workspace_bytes(p: Params, which: int) -> int:
+    return int(_lib.sale_workspace_bytes(ctypes.byref(p.c()), which))
+
+
+def status_string(status: int) -> str:
+    return _lib.sale_status_string(status).decode()
+
+
+def quantize_qk(p: Params, q: torch.Tensor, k: torch.Tensor, out=None):
+    """-> (q4 u8 [B,Hq,N,64], k4 u8 [B,Hkv,N,64], q_scale f32 [B,Hq,N/bq], k_scale f32 [B,Hkv,N/bk])"""
+    dev = q.device
+    if out is None:
+        q4 = torch.empty(p.batch, p.n_q_heads, p.seq_len, p.head_dim // 2, dtype=torch.uint8, device=dev)
+        k4 = torch.empty(p.batch, p.n_kv_heads, p.seq_len, p.head_dim // 2, dtype=torch.uint8, device=dev)
+        qs = torch.empty(p.batch, p.n_q_heads, p.seq_len // p.block_q, dtype=torch.float32, device=dev)
+        ks = torch.empty(p.batch, p.n_kv_heads, p.seq_len // p.block_k, dtype=torch.float32, device=dev)
+    else:
+        q4, k4, qs, ks = out
+    _check(_lib.sale_quantize_qk(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(qs), _ptr(ks), _stream()))
+    return q4, k4, qs, ks
+
+
+def select(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, want_stats: bool = False, out=None, ws=None):
+    """-> (block_mask int64-viewed-u64 [B,Hq,Nq,W], row_counts i32 [B,Hq,Nq], m~, l~ or None)"""
+    dev = q.device
+    if out is None:
+        mask = torch.empty(p.batch, p.n_q_heads, p.n_q, p.words, dtype=torch.int64, device=dev)
+        counts = torch.empty(p.batch, p.n_q_heads, p.n_q, dtype=torch.int32, device=dev)
+    else:
+        mask, counts = out
+    m = l = None
+    if want_stats:
+        m = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=dev)
+        l = torch.empty_like(m)
+    need = workspace_bytes(p, WS_SELECT)
+    if ws is None:
+        ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    _check(_lib.sale_select(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
+                            _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), _ptr(m), _ptr(l),
+                            _ptr(ws), ws.numel(), _stream()))
+    return mask, counts, m, l
+
+
+def sparse_attn(p: Params, q, k, v, block_mask, row_counts=None, want_lse: bool = False, out=None, ws=None):
+    """-> (o bf16 [B,Hq,N,d], lse f32 [B,Hq,N] or None)"""
+    o = torch.empty_like(q) if out is None else out
+    lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    need = workspace_bytes(p, WS_SPARSE_ATTN)
+    if ws is None and need > 0:
+        ws = torch.empty(need, dtype=torch.uint8, device=q.device)
+    _check(_lib.sale_sparse_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(block_mask), _ptr(row_counts),
+                                 _ptr(o), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
+    return o, lse
+
+
+def dense_attn(p: Params, q, k, v, want_lse: bool = False, out=None):
+    """-> (o bf16 [B,Hq,N,d], lse f32 [B,Hq,N] or None)"""
+    o = torch.empty_like(q) if out is None else out
+    lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    _check(_lib.sale_dense_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream()))
+    return o, lse
+
+
+def qk_int4_products(p: Params, q4, k4, q_head: int, q_block: int, k_block_begin: int, k_block_end: int):
+    """-> int32 [block_q, (k_block_end - k_block_begin) * block_k]"""
+    out = torch.empty(p.block_q, (k_block_end - k_block_begin) * p.block_k, dtype=torch.int32, device=q4.device)
+    _check(_lib.sale_qk_int4_products(ctypes.byref(p.c()), _ptr(q4), _ptr(k4), q_head, q_block,
+                                      k_block_begin, k_block_end, _ptr(out), _stream()))
+    return out

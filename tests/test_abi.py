@@ -1,0 +1,85 @@
+"""The C-ABI library loads without a GPU, exports every function the header
+declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sale.h")
+
+
+@pytest.fixture(scope="module")
+def sale():
+    from paper_2505_24179_amd import sale as mod
+    return mod
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sale_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(sale):
+    names = _declared_functions()
+    assert {"sale_quantize_qk", "sale_select", "sale_sparse_attn", "sale_dense_attn",
+            "sale_qk_int4_products", "sale_workspace_bytes", "sale_status_string"} <= set(names)
+    lib = sale.raw()
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in sale.h but not exported"
+    assert set(sale.EXPORTED) == set(names)
+
+
+def test_status_strings(sale):
+    assert sale.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, -5):
+        assert sale.status_string(s) not in ("ok", "unknown status")
+    assert sale.status_string(-99) == "unknown status"
+
+
+def test_workspace_sizes(sale):
+    p = sale.Params(1, 32, 8, 131072)
+    assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4
+    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 0
+    assert sale.workspace_bytes(sale.Params(1, 32, 8, 100), sale.WS_SELECT) == 0   # invalid geometry
+
+
+def _call_quant(sale, p, fake=0x1000):
+    f = ctypes.c_void_p(fake)
+    return sale.raw().sale_quantize_qk(ctypes.byref(p.c()), f, f, f, f, f, f, None)
+
+
+def test_argument_validation_launches_nothing(sale):
+    lib = sale.raw()
+    good = sale.Params(1, 4, 2, 256)
+    f = ctypes.c_void_p(0x1000)   # never dereferenced: every call below fails validation first
+    assert lib.sale_quantize_qk(ctypes.byref(good.c()), None, f, f, f, f, f, None) == -1
+    assert lib.sale_quantize_qk(None, f, f, f, f, f, f, None) == -1
+    assert _call_quant(sale, sale.Params(1, 4, 2, 250)) == -2          # N not a multiple of the block
+    assert _call_quant(sale, sale.Params(0, 4, 2, 256)) == -2
+    assert _call_quant(sale, sale.Params(1, 4, 3, 256)) == -2          # heads not divisible
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, head_dim=64)) == -3
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, block_q=16, block_k=16)) == -3
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, flags=8)) == -3
+    # select: paper-shape 64x32 blocks are not built yet; workspace too small; bad tau_len
+    sel = lib.sale_select
+    p6432 = sale.Params(1, 4, 2, 256, block_k=32, local_blocks=8)
+    assert sel(ctypes.byref(p6432.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 1 << 30, None) == -3
+    assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 16, None) == -4
+    assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None, 0, None) == -4
+    assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 3, f, f, None, None, f, 1 << 30, None) == -2
+    assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, None, 1, f, f, None, None, f, 1 << 30, None) == -1
+    # attention
+    assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, None, f, None, None) == -1
+    assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, None, None, f, None, None, 0, None) == -1
+    too_long = sale.Params(1, 1, 1, 64 * 64 * 64 + 64)
+    assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, None) == -3
+    # parity hook range checks
+    prod = lib.sale_qk_int4_products
+    assert prod(ctypes.byref(good.c()), f, f, 4, 0, 0, 1, f, None) == -2
+    assert prod(ctypes.byref(good.c()), f, f, 0, 4, 0, 1, f, None) == -2
+    assert prod(ctypes.byref(good.c()), f, f, 0, 0, 2, 1, f, None) == -2
+    assert prod(ctypes.byref(good.c()), f, f, 0, 0, 0, 5, f, None) == -2
+    assert prod(ctypes.byref(good.c()), f, f, 0, 0, 1, 1, f, None) == 0    # empty range: nothing to do

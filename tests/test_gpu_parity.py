@@ -1,0 +1,253 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs, element by element.
+
+Bars: codes, scales' bit patterns, integer products and masks bit-exact (mask
+decisions within 1e-5 relative of the threshold are counted separately);
+attention output max abs err <= 2e-2 and mean abs err <= 2e-3 for bf16 inputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sale_oracle as so
+from paper_2505_24179_amd import inputs
+from tests.parity_utils import (check_output, compare_mask_row, f32, oracle_quantize, words_to_bool)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sale():
+    from paper_2505_24179_amd import sale as mod
+    return mod
+
+
+def _dev(*ts):
+    return [t.unsqueeze(0).contiguous().cuda() for t in ts]
+
+
+CASES = {
+    "toy": inputs.TOY,                                                         # 1 head, N = 2048, 32 blocks
+    "gqa4-1k": inputs.scaled(inputs.LLAMA_32K, 1024, 8, 2, "gqa4-1k"),         # the Llama grouping, small
+    "gqa2-ragged": inputs.scaled(inputs.LLAMA_32K, 64 * 7, 6, 3, "gqa2-ragged"),  # 42 units: padding waves
+    "one-block": inputs.scaled(inputs.TOY, 64, 1, 1, "one-block"),             # N = one block: no middle blocks
+    "mha-3-blocks": inputs.scaled(inputs.TOY, 192, 2, 2, "mha-3-blocks"),
+    "gqa8-4k": inputs.scaled(inputs.LLAMA_32K, 4096 + 64, 8, 1, "gqa8-4k"),    # two mask words, ragged second word
+}
+
+
+@pytest.fixture(scope="module", params=list(CASES))
+def case(request, sale):
+    w = CASES[request.param]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    return w, p, q, k, v
+
+
+def test_quantize_bit_exact(case, sale):
+    w, p, q, k, v = case
+    qd, kd = _dev(q, k)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    torch.cuda.synchronize()
+    qc, oqs, kc, oks = oracle_quantize(q, k)
+    np.testing.assert_array_equal(q4[0].cpu().numpy(), so.pack_int4(qc))
+    np.testing.assert_array_equal(k4[0].cpu().numpy(), so.pack_int4(kc))
+    np.testing.assert_array_equal(qs[0].cpu().numpy().view(np.uint32), oqs.view(np.uint32))
+    np.testing.assert_array_equal(ks[0].cpu().numpy().view(np.uint32), oks.view(np.uint32))
+
+
+def test_quantize_zero_block_extremes_and_32_row_blocks(sale):
+    g = torch.Generator().manual_seed(7)
+    q = (torch.randn(2, 256, 128, generator=g) * 3).bfloat16()
+    k = torch.randn(1, 256, 128, generator=g).bfloat16()
+    q[0, 64:128] = 0                      # all-zero block
+    q[1, 0, 0] = 3.0e38                   # huge amax: everything else rounds to 0
+    k[0, 128:192] = torch.tensor(2.0 ** -126).bfloat16()   # tiny but non-zero block
+    for bq, bk in ((64, 64), (32, 32), (64, 32)):
+        p = sale.Params(1, 2, 1, 256, block_q=bq, block_k=bk, local_blocks=256 // bk)
+        qd, kd = _dev(q, k)
+        q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+        torch.cuda.synchronize()
+        qc, oqs, kc, oks = oracle_quantize(q, k, bq, bk)
+        np.testing.assert_array_equal(q4[0].cpu().numpy(), so.pack_int4(qc))
+        np.testing.assert_array_equal(k4[0].cpu().numpy(), so.pack_int4(kc))
+        np.testing.assert_array_equal(qs[0].cpu().numpy().view(np.uint32), oqs.view(np.uint32))
+        np.testing.assert_array_equal(ks[0].cpu().numpy().view(np.uint32), oks.view(np.uint32))
+
+
+def test_int4_products_bit_exact(case, sale):
+    w, p, q, k, v = case
+    qd, kd = _dev(q, k)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    qc, _, kc, _ = oracle_quantize(q, k)
+    n_q = p.n_q
+    for h in sorted({0, w.n_q_heads - 1}):
+        for i in sorted({0, n_q // 2, n_q - 1}):
+            got = sale.qk_int4_products(p, q4, k4, h, i, 0, p.n_k).cpu().numpy()
+            ref = so.int_products(qc[h][i * 64:(i + 1) * 64], kc[h // w.group])
+            np.testing.assert_array_equal(got, ref)
+
+
+def test_int4_products_extremes(sale):
+    """All codes +-7: |product| reaches 128 * 49 = 6272 in every element."""
+    p = sale.Params(1, 1, 1, 128)
+    rng = np.random.default_rng(0)
+    qc = rng.choice(np.array([-7, 7], np.int8), size=(128, 128))
+    kc = rng.choice(np.array([-7, 7], np.int8), size=(128, 128))
+    qc[0] = 7; kc[0] = 7; kc[1] = -7
+    q4 = torch.from_numpy(so.pack_int4(qc)).cuda()
+    k4 = torch.from_numpy(so.pack_int4(kc)).cuda()
+    got = sale.qk_int4_products(p, q4, k4, 0, 1, 0, 2).cpu().numpy()
+    np.testing.assert_array_equal(got, so.int_products(qc[64:128], kc))
+    got0 = sale.qk_int4_products(p, q4, k4, 0, 0, 0, 1).cpu().numpy()
+    assert got0[0, 0] == 6272 and got0[0, 1] == -6272
+
+
+def _oracle_select_all(w, q, k, tau, flags=0):
+    geo = so.Geometry(w.seq_len, w.head_dim, stats_causal=bool(flags & 1))
+    qc, qs, kc, ks = oracle_quantize(q, k)
+    qf, kf = f32(q), f32(k)
+    out = []
+    for h in range(w.n_q_heads):
+        g = h // w.group
+        out.append(so.select_head(geo, qf[h], kf[g], qc[h], kc[g], qs[h], ks[g], tau))
+    return geo, out
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+def test_select_mask_matches_oracle(case, sale, flags):
+    w, p0, q, k, v = case
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=flags)
+    qd, kd = _dev(q, k)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    mask, counts, m, l = sale.select(p, qd, kd, q4, k4, qs, ks, tau, want_stats=True)
+    torch.cuda.synchronize()
+    geo, ora = _oracle_select_all(w, q, k, w.tau, flags)
+    got = words_to_bool(mask[0].cpu().numpy(), p.n_k)
+    hard = soft = 0
+    for h in range(w.n_q_heads):
+        omask, margin, mthr, thr, om, ol = ora[h]
+        np.testing.assert_allclose(m[0, h].cpu().numpy(), om, rtol=2e-6, atol=2e-6)
+        np.testing.assert_allclose(l[0, h].cpu().numpy(), ol, rtol=2e-5)
+        for i in range(geo.n_q):
+            a, b = compare_mask_row(got[h, i], omask[i], margin[i], mthr[i])
+            hard += a; soft += b
+        np.testing.assert_array_equal(counts[0, h].cpu().numpy(), got[h].sum(axis=1))
+    print(f"[{w.name} flags={flags}] borderline mask differences: {soft}")
+    assert hard == 0
+    assert soft <= 2
+
+
+def test_select_per_head_tau(sale):
+    w = CASES["gqa4-1k"]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    qd, kd = _dev(q, k)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    taus = [0.0005 * 2 ** h for h in range(w.n_q_heads)]
+    tau = torch.tensor(taus, dtype=torch.float32, device="cuda")
+    mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+    got = words_to_bool(mask[0].cpu().numpy(), p.n_k)
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    qc, oqs, kc, oks = oracle_quantize(q, k)
+    qf, kf = f32(q), f32(k)
+    for h in range(w.n_q_heads):
+        g = h // w.group
+        omask, margin, mthr, *_ = so.select_head(geo, qf[h], kf[g], qc[h], kc[g], oqs[h], oks[g], float(np.float32(taus[h])))
+        for i in range(geo.n_q):
+            a, b = compare_mask_row(got[h, i], omask[i], margin[i], mthr[i])
+            assert a == 0
+
+
+def _oracle_attention(w, q, k, v, masks):
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    qf, kf, vf = f32(q), f32(k), f32(v)
+    o = np.zeros((w.n_q_heads, w.seq_len, w.head_dim))
+    lse = np.zeros((w.n_q_heads, w.seq_len))
+    for h in range(w.n_q_heads):
+        g = h // w.group
+        o[h], lse[h] = so.attention_head(geo, qf[h], kf[g], vf[g], masks[h])
+    return o, lse
+
+
+def test_dense_attention_matches_oracle(case, sale):
+    w, p, q, k, v = case
+    qd, kd, vd = _dev(q, k, v)
+    o, lse = sale.dense_attn(p, qd, kd, vd, want_lse=True)
+    torch.cuda.synchronize()
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    ref, ref_lse = _oracle_attention(w, q, k, v, [so.dense_mask(geo)] * w.n_q_heads)
+    mx, mean = check_output(f32(o[0]), ref, f"dense {w.name}")
+    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+    print(f"[{w.name}] dense max abs {mx:.3g} mean abs {mean:.3g}")
+
+
+def test_sparse_attention_matches_oracle_on_selected_mask(case, sale):
+    w, p, q, k, v = case
+    qd, kd, vd = _dev(q, k, v)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+    o, lse = sale.sparse_attn(p, qd, kd, vd, mask, counts, want_lse=True)
+    torch.cuda.synchronize()
+    # the oracle attends over the mask the GPU produced (mask parity is its own test)
+    got = words_to_bool(mask[0].cpu().numpy(), p.n_k)
+    ref, ref_lse = _oracle_attention(w, q, k, v, got)
+    mx, mean = check_output(f32(o[0]), ref, f"sparse {w.name}")
+    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+    print(f"[{w.name}] sparse max abs {mx:.3g} mean abs {mean:.3g}")
+
+
+def test_sparse_attention_random_masks_and_all_ones(sale):
+    """Masks the Selection-Pass would not produce: random per-head patterns
+    (diagonal kept), and all ones, which must equal the dense kernel bit for bit."""
+    w = CASES["gqa4-1k"]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    qd, kd, vd = _dev(q, k, v)
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    rng = np.random.default_rng(3)
+    dm = so.dense_mask(geo)
+    masks = []
+    for h in range(w.n_q_heads):
+        mk = dm & (rng.random(dm.shape) < 0.3)
+        mk[np.arange(geo.n_q), np.arange(geo.n_q)] = True
+        masks.append(mk)
+    words = np.stack([np.stack([so.pack_mask_words(mk[i]) for i in range(geo.n_q)]) for mk in masks])
+    # set garbage above the diagonal: the kernel must ignore it
+    words_garbage = words.copy()
+    for i in range(geo.n_q):
+        words_garbage[:, i, 0] |= np.uint64(0xFFFFFFFFFFFFFFFF) << np.uint64(i + 1) if i < 63 else np.uint64(0)
+    wd = torch.from_numpy(words_garbage.view(np.int64)).unsqueeze(0).cuda()
+    o, _ = sale.sparse_attn(p, qd, kd, vd, wd)
+    ref, _ = _oracle_attention(w, q, k, v, masks)
+    check_output(f32(o[0]), ref, "random masks")
+    ones = torch.full((1, w.n_q_heads, geo.n_q, p.words), -1, dtype=torch.int64, device="cuda")
+    o1, _ = sale.sparse_attn(p, qd, kd, vd, ones)
+    o2, _ = sale.dense_attn(p, qd, kd, vd)
+    assert torch.equal(o1, o2)
+
+
+def test_batch_two_equals_two_single_batches(sale):
+    w = CASES["gqa2-ragged"]
+    q, k, v = inputs.make_inputs(w)
+    w2 = inputs.scaled(w, w.seq_len, name="b2")
+    q2, k2, v2 = inputs.make_inputs(inputs.Workload(**{**w2.__dict__, "seed": w.seed + 17}))
+    qb = torch.stack([q, q2]).cuda(); kb = torch.stack([k, k2]).cuda(); vb = torch.stack([v, v2]).cuda()
+    p2 = sale.Params(2, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    p1 = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    q4, k4, qs, ks = sale.quantize_qk(p2, qb, kb)
+    mask, counts, _, _ = sale.select(p2, qb, kb, q4, k4, qs, ks, tau)
+    o, _ = sale.sparse_attn(p2, qb, kb, vb, mask, counts)
+    for b in range(2):
+        qq, kk, vv = qb[b:b + 1].contiguous(), kb[b:b + 1].contiguous(), vb[b:b + 1].contiguous()
+        a4, b4, as_, bs_ = sale.quantize_qk(p1, qq, kk)
+        assert torch.equal(a4[0], q4[b]) and torch.equal(b4[0], k4[b]) and torch.equal(as_[0], qs[b])
+        mk, ct, _, _ = sale.select(p1, qq, kk, a4, b4, as_, bs_, tau)
+        assert torch.equal(mk[0], mask[b]) and torch.equal(ct[0], counts[b])
+        ob, _ = sale.sparse_attn(p1, qq, kk, vv, mk, ct)
+        assert torch.equal(ob[0], o[b])
