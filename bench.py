@@ -131,12 +131,12 @@ def main() -> int:
     # dense denominator
     dense_ms = None
     if args.dense_steps > 0:
-        sale.dense_attn(p, qd, kd, vd, out=o)
+        sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for _ in range(args.dense_steps):
-            sale.dense_attn(p, qd, kd, vd, out=o)
+            sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
         b.record()
         torch.cuda.synchronize()
         dense_ms = a.elapsed_time(b) / args.dense_steps

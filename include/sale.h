@@ -70,6 +70,7 @@ typedef struct sale_params {
 /* Which call a workspace is for. */
 #define SALE_WS_SELECT 1
 #define SALE_WS_SPARSE_ATTN 2
+#define SALE_WS_DENSE_ATTN 3
 
 /* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
  * parameters are invalid). */
@@ -138,7 +139,8 @@ int sale_select(const sale_params_t* p, const void* q, const void* k,
  *   lse        out: optional (may be NULL) fp32 [batch][n_q_heads][N], natural-log
  *                   sum-exp of the kept logits of each row
  *   ws            : workspace of sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN) bytes
- *                   (may be NULL when that size is 0)
+ *                   (K and V are copied into it once per call in the kernel's
+ *                   operand order; 2 * sizeof(K) bytes)
  */
 int sale_sparse_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
                      const uint64_t* block_mask, const int32_t* row_counts,
@@ -147,9 +149,10 @@ int sale_sparse_attn(const sale_params_t* p, const void* q, const void* k, const
 /*
  * Dense causal attention (Eq. 1 with M = M_c): the same kernel with every
  * causally visible block kept.  The denominator of every reported speed-up.
+ *   ws : workspace of sale_workspace_bytes(p, SALE_WS_DENSE_ATTN) bytes
  */
 int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
-                    void* o, float* lse, void* stream);
+                    void* o, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Parity hook: the exact integer products of the Selection-Pass,

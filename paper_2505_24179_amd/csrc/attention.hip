@@ -3,70 +3,138 @@
 //
 // Design for gfx950
 // -----------------
-// * One workgroup = 4 waves = 4 units (query head, 64-row query block) that
-//   share one KV head: with GQA group 4 these are the 4 query heads of the
-//   group at the same query block, so every K/V tile staged in LDS feeds 256
-//   query rows.  Workgroups are dealt round-robin over KV heads (blockIdx %
-//   n_kv_heads: one KV head per XCD / L2 when there are 8) and longest rows
-//   first.
-// * The workgroup walks the UNION of its waves' mask rows; a wave whose own bit
-//   is clear skips the tile's arithmetic (a skipped block costs that wave
-//   nothing but the barrier).  The dense kernel is the same code with the
-//   causal mask synthesised in place of a loaded one.
+// * One wave = one unit (query head, 64-row query block) walking its OWN mask
+//   row.  The masks of the query heads that share a KV head differ block by
+//   block, so staging a tile once for several heads only pays when their bits
+//   coincide; instead each wave streams the operands of exactly the blocks its
+//   row keeps straight from global memory into MFMA operand registers: no LDS
+//   staging, no barriers, a skipped block costs nothing.
+// * To make those loads full 1 KB coalesced transactions (and to get V
+//   transposed for free) a pre-pass copies K and V once into "fragment order"
+//   (layouts at rearrange_kv_kernel).
 // * Each wave computes the TRANSPOSED score tile S^T = K Q^T (keys x queries)
 //   with v_mfma_f32_32x32x16_bf16: a lane then owns 16 keys of one query
 //   column, so row max / row sum / rescale factors are per-lane scalars and
 //   the only cross-lane traffic of the online softmax is one exchange with
 //   lane^32.  The accumulator layout of S^T is, register for register, the B
 //   operand layout of the second product O^T = V^T P^T (up to a permutation
-//   of the contraction index that is applied to V^T as well), so P never
-//   leaves registers.  V^T operands come straight from the row-major V tile
-//   with the LDS transpose read ds_read_b64_tr_b16.
-// * Softmax in fp32 with exp2 and the scale folded in; O accumulates in fp32.
+//   of the contraction index that the V copy applies as well), so P never
+//   leaves registers.
+// * Softmax in fp32 with exp2 and the scale folded in; the O rescale is skipped
+//   (exactly) whenever no row maximum grew; O accumulates in fp32.
+// * Locality: a workgroup is 4 units of one KV head at the same query block
+//   (the GQA group), workgroups go round-robin over KV heads (blockIdx %
+//   n_kv_heads: one KV head per XCD / L2 when there are 8), longest rows first,
+//   and the grid is issued in rounds of one workgroup per CU.  All units of a
+//   round start together and sweep their lists in ascending key order at the
+//   same average pace, so the units of one KV head meet in the same L2 window
+//   and a block kept by many rows is fetched from HBM once per round.
+#include <stdlib.h>
+
 #include "sale_common.h"
 
 namespace sale {
 
-constexpr int KS = 136;   // LDS row stride of the K tile in elements (272 B: conflict-free 16-byte row reads)
-constexpr int VS = 144;   // LDS row stride of the V tile in elements (288 B: conflict-free transpose reads)
+// ---------------------------------------------------------------------------
+// Computation-Pass proper: every wave walks its OWN mask row.
+//
+// The masks of the query heads that share a KV head differ block by block, so
+// staging a tile once for several heads only pays when their bits coincide.
+// Here each wave streams the operands of exactly the blocks its row keeps,
+// straight from global memory into MFMA operand registers: no LDS, no
+// barriers, a skipped block costs nothing.  To make those loads full 1 KB
+// coalesced transactions (and to get V transposed for free) a pre-pass copies
+// K and V once into "fragment order":
+//   K' [kv head][block j][mt 0..1][s 0..7][lane 0..63] : 8 channels 16s + 8(lane/32).. of key row 32mt + lane%32
+//   V' [kv head][block j][dt 0..3][s 0..3][lane 0..63] : channel 32dt + lane%32 of the 8 keys
+//                                                        16s + 8(e/4) + 4(lane/32) + e%4,  e = 0..7
+// (the key order inside V' is the order in which the S^T accumulator registers
+// hand P^T to the second product).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16_t* __restrict__ k,
+                                                           const uint16_t* __restrict__ v, u32x4* __restrict__ kp,
+                                                           u32x4* __restrict__ vp) {
+  __shared__ uint16_t sv[64 * (kHeadDim + 2)];
+  const int tid = threadIdx.x;
+  const size_t tile = blockIdx.x;                      // flattened (kv head, block j): rows tile*64 .. +63
+  const uint16_t* kt = k + tile * 64 * kHeadDim;
+  const uint16_t* vt = v + tile * 64 * kHeadDim;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int chunk = tid + 256 * r;                   // V tile -> LDS, rows padded by one bank
+    const int row = chunk >> 4, col = (chunk & 15) * 8;
+    const u32x4 w = *(const u32x4*)(vt + row * kHeadDim + col);
+    uint32_t* d = (uint32_t*)&sv[row * (kHeadDim + 2) + col];
+    d[0] = w[0]; d[1] = w[1]; d[2] = w[2]; d[3] = w[3];
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int oc = tid + 256 * r;
+    const int lane = oc & 63, s = (oc >> 6) & 7, mt = oc >> 9;
+    kp[tile * 1024 + oc] = *(const u32x4*)(kt + (32 * mt + (lane & 31)) * kHeadDim + 16 * s + 8 * (lane >> 5));
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int oc = tid + 256 * r;
+    const int lane = oc & 63, s = (oc >> 6) & 3, dt = oc >> 8;
+    const int d = 32 * dt + (lane & 31), h = lane >> 5;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int e = 2 * e2;
+      const int key = 16 * s + 8 * (e >> 2) + 4 * h + (e & 3);
+      w[e2] = (uint32_t)sv[key * (kHeadDim + 2) + d] | ((uint32_t)sv[(key + 1) * (kHeadDim + 2) + d] << 16);
+    }
+    u32x4 out;
+    out[0] = w[0]; out[1] = w[1]; out[2] = w[2]; out[3] = w[3];
+    vp[tile * 1024 + oc] = out;
+  }
+}
 
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-__global__ __launch_bounds__(256) void attn_kernel(Geo g, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                                                   const uint16_t* __restrict__ v, const uint64_t* __restrict__ mask,
-                                                   uint16_t* __restrict__ o, float* __restrict__ lse) {
-  __shared__ __attribute__((aligned(16))) uint16_t sK[64 * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[64 * VS];
-  __shared__ uint64_t sWords[4][kMaskWordsMax];
-  __shared__ uint64_t sUnion[kMaskWordsMax];
-
+// One launch covers the key blocks of mask words [win_begin, win_begin + win_words) ("window").  A unit
+// whose row keeps blocks before the window resumes from the state (fp32 O^T accumulators, running max
+// and sum) an earlier launch parked in st_o / st_ml; one that keeps blocks after it parks its state
+// there instead of writing O.  With a single window covering the whole row no state is touched.
+__global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, int win_words,
+                                                        const uint16_t* __restrict__ q,
+                                                        const bf16x8* __restrict__ kp, const bf16x8* __restrict__ vp,
+                                                        const uint64_t* __restrict__ mask, uint16_t* __restrict__ o,
+                                                        float* __restrict__ lse, f32x4* __restrict__ st_o,
+                                                        float* __restrict__ st_ml) {
+  __shared__ bf16x8 sQ[4][16][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 31, h = lane >> 5;
   const Unit u = unit_of(g, blockIdx.x, wave);
+  if (!u.valid) return;
 
-  // ---- mask rows of the four units and their union -------------------------------------
-  for (int wc = lane; wc < g.words; wc += 64) {
-    uint64_t word = 0;
-    if (u.valid) {
-      const int lo = wc * 64;
-      const uint64_t causal = u.i >= lo + 63 ? ~0ull : (u.i < lo ? 0ull : ((2ull << (u.i - lo)) - 1ull));
-      word = mask ? (mask[((size_t)u.qh * g.n_qb + u.i) * g.words + wc] & causal) : causal;
-    }
-    sWords[wave][wc] = word;
-  }
-  __syncthreads();
-  for (int wc = tid; wc < g.words; wc += 256) sUnion[wc] = sWords[0][wc] | sWords[1][wc] | sWords[2][wc] | sWords[3][wc];
-  __syncthreads();
+  // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
+  const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
+  const int last_word = u.i >> 6;
+  auto row_word = [&](int wc) -> uint64_t {
+    const int lo = wc * 64;
+    const uint64_t causal = u.i >= lo + 63 ? ~0ull : ((2ull << (u.i - lo)) - 1ull);
+    return mrow ? (mrow[wc] & causal) : causal;
+  };
+  if (win_begin > last_word) return;
+  const int win_end = min(win_begin + win_words, last_word + 1);   // exclusive
+  bool any_before = false, any_in = false, any_after = false;
+  for (int wc = 0; wc < win_begin; ++wc) any_before = any_before || row_word(wc) != 0;
+  for (int wc = win_begin; wc < win_end; ++wc) any_in = any_in || row_word(wc) != 0;
+  for (int wc = win_end; wc <= last_word; ++wc) any_after = any_after || row_word(wc) != 0;
+  // A window without kept blocks leaves the row's state alone; a row without any kept block at
+  // all writes its zeros in the launch of its last window.
+  if (!any_in && (any_before || any_after || win_end != last_word + 1)) return;
 
-  // ---- Q as the B operand of S^T = K Q^T ------------------------------------------------
-  bf16x8 qf[2][8];
+  // Q fragments (B operand of S^T = K Q^T) live in LDS, each lane's own 16 x 16 bytes: they are
+  // re-read every tile, which frees 64 registers per lane for the K / V operand prefetch.
+  bf16x8* qs = &sQ[wave][0][lane];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
+    for (int s = 0; s < 8; ++s) qs[(nt * 8 + s) * 64] = *(const bf16x8*)(row + 16 * s);
   }
-
   f32x16 oacc[4][2];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -76,131 +144,153 @@ __global__ __launch_bounds__(256) void attn_kernel(Geo g, const uint16_t* __rest
       for (int r = 0; r < 16; ++r) oacc[dt][nt][r] = 0.0f;
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   const float cs = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(d)
+  const size_t unit_flat = (size_t)u.qh * g.n_qb + u.i;
+  f32x4* so = st_o + unit_flat * (32 * 64) + lane;          // [dt][nt][quarter][lane] 16-byte chunks
+  float* sml = st_ml + unit_flat * 256 + lane;               // [m nt0, m nt1, l nt0, l nt1][lane]
+  if (any_before) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const f32x4 w = __builtin_nontemporal_load(&so[((dt * 2 + nt) * 4 + qd) * 64]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) oacc[dt][nt][4 * qd + e] = w[e];
+        }
+    m_run[0] = sml[0]; m_run[1] = sml[64]; l_run[0] = sml[128]; l_run[1] = sml[192];
+  }
 
-  // ---- iteration over the union of kept blocks ------------------------------------------
-  int wc_it = 0;
-  uint64_t cur = sUnion[0];
+  int wc_it = win_begin;
+  uint64_t cur = row_word(win_begin);
   auto next_block = [&]() -> int {
     while (cur == 0) {
-      if (++wc_it >= g.words) return -1;
-      cur = sUnion[wc_it];
+      if (++wc_it >= win_end) return -1;
+      cur = row_word(wc_it);
     }
     const int b = __builtin_ctzll(cur);
     cur &= cur - 1;
     return wc_it * 64 + b;
   };
 
-  const uint16_t* kh = k + (size_t)u.kvh * g.seq * kHeadDim;
-  const uint16_t* vh = v + (size_t)u.kvh * g.seq * kHeadDim;
-  uint4 kreg[4], vreg[4];
-  auto load_tile = [&](int j) {
+  const bf16x8* kt = kp + (size_t)u.kvh * g.n_kb * 1024 + lane;
+  const bf16x8* vt = vp + (size_t)u.kvh * g.n_kb * 1024 + lane;
+  bf16x8 kf[2][8], vf[4][4];
+  auto load_k = [&](int j) {
+    const bf16x8* t = kt + (size_t)j * 1024;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int chunk = tid + 256 * t;
-      const size_t off = ((size_t)j * 64 + (chunk >> 4)) * kHeadDim + (chunk & 15) * 8;
-      kreg[t] = *(const uint4*)(kh + off);
-      vreg[t] = *(const uint4*)(vh + off);
-    }
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int s = 0; s < 8; ++s) kf[mt][s] = t[(mt * 8 + s) * 64];
   };
-  auto store_tile = [&]() {
+  auto load_v = [&](int j) {
+    const bf16x8* t = vt + (size_t)j * 1024;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int chunk = tid + 256 * t;
-      const int row = chunk >> 4, col = (chunk & 15) * 8;
-      *(uint4*)&sK[row * KS + col] = kreg[t];
-      *(uint4*)&sV[row * VS + col] = vreg[t];
-    }
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) vf[dt][s] = t[(dt * 4 + s) * 64];
   };
 
   int j_cur = next_block();
-  if (j_cur >= 0) load_tile(j_cur);
+  if (j_cur >= 0) { load_k(j_cur); load_v(j_cur); }
   while (j_cur >= 0) {
-    store_tile();
-    __syncthreads();
     const int j_next = next_block();
-    if (j_next >= 0) load_tile(j_next);
+    const int j_load = j_next >= 0 ? j_next : j_cur;
 
-    const bool active = (sWords[wave][j_cur >> 6] >> (j_cur & 63)) & 1ull;
-    if (active) {
-      // S^T tile: keys x queries
-      f32x16 sacc[2][2];
+    f32x16 sacc[2][2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+      for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[mt][nt][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) sacc[mt][nt][r] = 0.0f;
+    int q_off = 0;
+    asm volatile("" : "+v"(q_off));   // opaque: keeps the Q reads inside the loop (they would be hoisted back into registers)
+    const bf16x8* qt = qs + q_off;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 q0 = qt[s * 64], q1 = qt[(8 + s) * 64];
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          const bf16x8 a = *(const bf16x8*)&sK[(32 * mt + c) * KS + 16 * s + 8 * h];
-          sacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][s], sacc[mt][0], 0, 0, 0);
-          sacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][s], sacc[mt][1], 0, 0, 0);
-        }
+        sacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], q0, sacc[mt][0], 0, 0, 0);
+        sacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], q1, sacc[mt][1], 0, 0, 0);
       }
-      const bool diag = j_cur == u.i;
-      bf16x8 pf[2][4];
+    }
+    load_k(j_load);
+
+    const bool diag = j_cur == u.i;
+    bf16x8 pf[2][4];
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        if (diag) {
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) sacc[mt][nt][r] = -INFINITY;
-        }
-        float mx = sacc[0][nt][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[0][nt][r]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[1][nt][r]);
-        mx = fmaxf(mx, swap_half(mx));
-        const float m_new = fmaxf(m_run[nt], mx);          // finite: key 0 of a kept block is visible to every row
-        const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
-        const float mb = m_new * cs;
-        float sum = 0.0f;
+    for (int nt = 0; nt < 2; ++nt) {
+      if (diag) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(sacc[mt][nt][r] * cs - mb);
-            sacc[mt][nt][r] = p;
-            sum += p;
-          }
-        l_run[nt] = l_run[nt] * alpha + sum;
+          for (int r = 0; r < 16; ++r)
+            if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) sacc[mt][nt][r] = -INFINITY;
+      }
+      float mx = fmaxf(sacc[0][nt][0], sacc[1][nt][0]);
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][nt][r]), sacc[1][nt][r]);
+      mx = fmaxf(mx, swap_half(mx));
+      // Rescale only when some row's maximum grew (exact: otherwise the factor is 1).
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[nt]) != 0ull) {
+        const float m_new = fmaxf(m_run[nt], mx);        // finite: key 0 of a kept block is visible to every row
+        const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
+        l_run[nt] *= alpha;
         m_run[nt] = m_new;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
-        // P^T as the B operand of O^T = V^T P^T: k-step s takes registers 8*(s%2).. of tile s/2
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) pf[nt][s][e] = (__bf16)sacc[s >> 1][nt][8 * (s & 1) + e];
       }
-      // O^T += V^T P^T.  k-step s, lane half h covers keys 16s + 4h + {0..3} and 16s + 8 + 4h + {0..3}.
-      const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+      const float mb = m_run[nt] * cs;
+      bf16x2 ones;
+      ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+      float sum = l_run[nt];
+      // P^T as the B operand of O^T = V^T P^T: k-step s takes registers 8*(s%2).. of tile s/2
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
+        u32x4 packed;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          const uint16_t* pa = &sV[(16 * s + 4 * h + tr_row) * VS + 32 * dt + tr_col];
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)pa);
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(pa + 8 * VS));
-          const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-          oacc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][s], oacc[dt][0], 0, 0, 0);
-          oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][s], oacc[dt][1], 0, 0, 0);
+        for (int e2 = 0; e2 < 4; ++e2) {
+          const int r = 8 * (s & 1) + 2 * e2;
+          bf16x2 pk;
+          pk[0] = (__bf16)__builtin_amdgcn_exp2f(sacc[s >> 1][nt][r] * cs - mb);
+          pk[1] = (__bf16)__builtin_amdgcn_exp2f(sacc[s >> 1][nt][r + 1] * cs - mb);
+          sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);   // row sum of the rounded P
+          packed[e2] = __builtin_bit_cast(unsigned, pk);
         }
+        pf[nt][s] = __builtin_bit_cast(bf16x8, packed);
       }
+      l_run[nt] = sum;
     }
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+          oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], pf[nt][s], oacc[dt][nt], 0, 0, 0);
+    load_v(j_load);
     j_cur = j_next;
   }
 
-  // ---- epilogue ---------------------------------------------------------------------------
-  if (!u.valid) return;
+  if (any_after) {
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          f32x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = oacc[dt][nt][4 * qd + e];
+          __builtin_nontemporal_store(w, &so[((dt * 2 + nt) * 4 + qd) * 64]);
+        }
+    sml[0] = m_run[0]; sml[64] = m_run[1]; sml[128] = l_run[0]; sml[192] = l_run[1];
+    return;
+  }
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_run[nt] + swap_half(l_run[nt]);
@@ -220,13 +310,34 @@ __global__ __launch_bounds__(256) void attn_kernel(Geo g, const uint16_t* __rest
   }
 }
 
-static int launch_attn(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask, void* o,
-                       float* lse, hipStream_t st) {
+static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
+                            void* o, float* lse, void* ws, hipStream_t st) {
   const Geo g = make_geo(p);
+  const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
+  u32x4* kp = (u32x4*)ws;
+  u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
+  rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * g.n_kb)), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
+                                                                              (const uint16_t*)v, kp, vp);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const int tiles = (g.n_qb * g.group + 3) / 4;
-  attn_kernel<<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k,
-                                                                      (const uint16_t*)v, mask, (uint16_t*)o, lse);
-  return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
+  f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
+  float* st_ml = (float*)st_o + (size_t)g.n_qh * g.n_qb * (128 * 64);
+  // The dense kernel sweeps every row in one launch: neighbouring rows read the same blocks at the same
+  // time anyway.  A sparse row keeps a scattered subset, so the sweep is cut into windows of key blocks
+  // small enough for the window's K', V' of one KV head to stay in its XCD's L2; the rows' accumulators
+  // are parked in the workspace between windows.
+  const char* e = getenv("SALE_WIN_WORDS");
+  const int win_words = mask ? (e ? atoi(e) : 2) : g.words;
+  for (int wb = 0; wb < g.words; wb += win_words) {
+    // units are dealt longest rows first: those that end before this window sit at the end of the grid
+    const int t_min = (wb * 64 * g.group) / 4;
+    const int nb = (tiles - t_min) * g.n_kvh;
+    if (nb <= 0) break;
+    attn_rows_kernel<<<dim3((unsigned)nb), dim3(256), 0, st>>>(g, wb, win_words, (const uint16_t*)q, (const bf16x8*)kp,
+                                                               (const bf16x8*)vp, mask, (uint16_t*)o, lse, st_o, st_ml);
+    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  }
+  return SALE_OK;
 }
 
 }  // namespace sale
@@ -241,14 +352,16 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
-  if (need > 0 && (!ws || ws_bytes < need)) return SALE_ERR_WORKSPACE;
-  return launch_attn(p, q, k, v, block_mask, o, lse, (hipStream_t)stream);
+  if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
+  return launch_attn_rows(p, q, k, v, block_mask, o, lse, ws, (hipStream_t)stream);
 }
 
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
-                               void* stream) {
+                               void* ws, size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !o) return SALE_ERR_NULL_ARG;
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
-  return launch_attn(p, q, k, v, nullptr, o, lse, (hipStream_t)stream);
+  const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
+  if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
+  return launch_attn_rows(p, q, k, v, nullptr, o, lse, ws, (hipStream_t)stream);
 }

@@ -78,6 +78,19 @@ __device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
   return u;
 }
 
+__device__ __forceinline__ Unit unit_of_kv_major(const Geo& g, int block, int wave) {
+  const int units = g.n_qb * g.group;
+  const int tiles = (units + 3) / 4;
+  Unit u;
+  u.kvh = block / tiles;
+  const int t = tiles - 1 - block % tiles;
+  const int id = t * 4 + wave;
+  u.valid = id < units;
+  u.i = u.valid ? id / g.group : 0;
+  u.qh = u.kvh * g.group + (u.valid ? id % g.group : 0);
+  return u;
+}
+
 int validate_common(const sale_params_t* p, bool need_64x64);
 Geo make_geo(const sale_params_t* p);
 

@@ -23,6 +23,7 @@ OK = 0
 FLAG_STATS_CAUSAL = 1
 WS_SELECT = 1
 WS_SPARSE_ATTN = 2
+WS_DENSE_ATTN = 3
 
 
 class _Params(ctypes.Structure):
@@ -69,7 +70,7 @@ _SIGS = {
     "sale_quantize_qk": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "sale_select": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_sparse_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
-    "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
@@ -151,19 +152,21 @@ def sparse_attn(p: Params, q, k, v, block_mask, row_counts=None, want_lse: bool 
     """-> (o bf16 [B,Hq,N,d], lse f32 [B,Hq,N] or None)"""
     o = torch.empty_like(q) if out is None else out
     lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
-    need = workspace_bytes(p, WS_SPARSE_ATTN)
-    if ws is None and need > 0:
-        ws = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if ws is None:
+        ws = torch.empty(max(1, workspace_bytes(p, WS_SPARSE_ATTN)), dtype=torch.uint8, device=q.device)
     _check(_lib.sale_sparse_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(block_mask), _ptr(row_counts),
                                  _ptr(o), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
     return o, lse
 
 
-def dense_attn(p: Params, q, k, v, want_lse: bool = False, out=None):
+def dense_attn(p: Params, q, k, v, want_lse: bool = False, out=None, ws=None):
     """-> (o bf16 [B,Hq,N,d], lse f32 [B,Hq,N] or None)"""
     o = torch.empty_like(q) if out is None else out
     lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
-    _check(_lib.sale_dense_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream()))
+    if ws is None:
+        ws = torch.empty(max(1, workspace_bytes(p, WS_DENSE_ATTN)), dtype=torch.uint8, device=q.device)
+    _check(_lib.sale_dense_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                _ptr(ws), ws.numel(), _stream()))
     return o, lse
 
 

@@ -42,7 +42,8 @@ def test_status_strings(sale):
 def test_workspace_sizes(sale):
     p = sale.Params(1, 32, 8, 131072)
     assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4
-    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 0
+    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 2 * 8 * 131072 * 128 * 2 + 32 * 131072 * 132 * 4
+    assert sale.workspace_bytes(p, sale.WS_DENSE_ATTN) == 2 * 8 * 131072 * 128 * 2
     assert sale.workspace_bytes(sale.Params(1, 32, 8, 100), sale.WS_SELECT) == 0   # invalid geometry
 
 
@@ -72,10 +73,12 @@ def test_argument_validation_launches_nothing(sale):
     assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 3, f, f, None, None, f, 1 << 30, None) == -2
     assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, None, 1, f, f, None, None, f, 1 << 30, None) == -1
     # attention
-    assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, None, f, None, None) == -1
-    assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, None, None, f, None, None, 0, None) == -1
+    assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, None, f, None, f, 1 << 30, None) == -1
+    assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, f, f, None, f, 16, None) == -4
+    assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, None, None, f, None, f, 1 << 30, None) == -1
+    assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, f, None, f, None, None, 0, None) == -4
     too_long = sale.Params(1, 1, 1, 64 * 64 * 64 + 64)
-    assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, None) == -3
+    assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, f, 1 << 40, None) == -3
     # parity hook range checks
     prod = lib.sale_qk_int4_products
     assert prod(ctypes.byref(good.c()), f, f, 4, 0, 0, 1, f, None) == -2
