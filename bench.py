@@ -70,7 +70,7 @@ def main() -> int:
     ap.add_argument("--dense-steps", type=int, default=2)
     ap.add_argument("--workload", default="llama31-8b-layer-128k")
     ap.add_argument("--tau", type=float, default=None)
-    ap.add_argument("--cpu-units", type=int, default=24, help="oracle sample size (0 = skip the CPU baseline)")
+    ap.add_argument("--cpu-units", type=int, default=96, help="oracle sample size (0 = skip the CPU baseline)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards by KV head without communication, "

@@ -51,7 +51,7 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
     case SALE_WS_SPARSE_ATTN:   // K and V copied once into MFMA fragment order
     case SALE_WS_DENSE_ATTN:
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
-             (which_call == SALE_WS_SPARSE_ATTN ? rows * (kHeadDim + 4) * sizeof(float) : 0);   // parked row state
+             (which_call == SALE_WS_SPARSE_ATTN ? (rows / kBlockQ) * sizeof(int32_t) : 0);   // unit order
     default:
       return 0;
   }

@@ -22,15 +22,14 @@
 //   leaves registers.
 // * Softmax in fp32 with exp2 and the scale folded in; the O rescale is skipped
 //   (exactly) whenever no row maximum grew; O accumulates in fp32.
-// * Locality: a workgroup is 4 units of one KV head at the same query block
-//   (the GQA group), workgroups go round-robin over KV heads (blockIdx %
-//   n_kv_heads: one KV head per XCD / L2 when there are 8), longest rows first,
-//   and the grid is issued in rounds of one workgroup per CU.  All units of a
-//   round start together and sweep their lists in ascending key order at the
-//   same average pace, so the units of one KV head meet in the same L2 window
-//   and a block kept by many rows is fetched from HBM once per round.
-#include <stdlib.h>
-
+// * Scheduling.  Dense: a workgroup is the 4 units of one GQA group at the same
+//   query block (they read the same blocks in step, so three of four loads hit
+//   L1), longest rows first.  Sparse: row lengths are heavy-tailed (a query
+//   block with one weak row keeps everything), so every unit is its own
+//   64-thread workgroup and the units of each KV head are issued in order of
+//   decreasing kept-block count (a counting sort of row_counts).  In both,
+//   workgroups go round-robin over KV heads (blockIdx % n_kv_heads: one KV
+//   head per XCD / L2 when there are 8).
 #include "sale_common.h"
 
 namespace sale {
@@ -92,20 +91,27 @@ __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16
   }
 }
 
-// One launch covers the key blocks of mask words [win_begin, win_begin + win_words) ("window").  A unit
-// whose row keeps blocks before the window resumes from the state (fp32 O^T accumulators, running max
-// and sum) an earlier launch parked in st_o / st_ml; one that keeps blocks after it parks its state
-// there instead of writing O.  With a single window covering the whole row no state is touched.
-__global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, int win_words,
-                                                        const uint16_t* __restrict__ q,
-                                                        const bf16x8* __restrict__ kp, const bf16x8* __restrict__ vp,
-                                                        const uint64_t* __restrict__ mask, uint16_t* __restrict__ o,
-                                                        float* __restrict__ lse, f32x4* __restrict__ st_o,
-                                                        float* __restrict__ st_ml) {
-  __shared__ bf16x8 sQ[4][16][64];
+// order: optional [kv head][rank] -> unit id within the KV head (block * group + head-in-group).
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
+                                                               const bf16x8* __restrict__ kp,
+                                                               const bf16x8* __restrict__ vp,
+                                                               const uint64_t* __restrict__ mask,
+                                                               const int32_t* __restrict__ order,
+                                                               uint16_t* __restrict__ o, float* __restrict__ lse) {
+  __shared__ bf16x8 sQ[WAVES][16][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 31, h = lane >> 5;
-  const Unit u = unit_of(g, blockIdx.x, wave);
+  const int units = g.n_qb * g.group;
+  Unit u;
+  {
+    u.kvh = blockIdx.x % g.n_kvh;
+    const int rank = (blockIdx.x / g.n_kvh) * WAVES + wave;
+    u.valid = rank < units;
+    const int id = !u.valid ? 0 : (order ? order[(size_t)u.kvh * units + rank] : units - 1 - rank);
+    u.i = id / g.group;
+    u.qh = u.kvh * g.group + id % g.group;
+  }
   if (!u.valid) return;
 
   // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
@@ -116,15 +122,6 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, in
     const uint64_t causal = u.i >= lo + 63 ? ~0ull : ((2ull << (u.i - lo)) - 1ull);
     return mrow ? (mrow[wc] & causal) : causal;
   };
-  if (win_begin > last_word) return;
-  const int win_end = min(win_begin + win_words, last_word + 1);   // exclusive
-  bool any_before = false, any_in = false, any_after = false;
-  for (int wc = 0; wc < win_begin; ++wc) any_before = any_before || row_word(wc) != 0;
-  for (int wc = win_begin; wc < win_end; ++wc) any_in = any_in || row_word(wc) != 0;
-  for (int wc = win_end; wc <= last_word; ++wc) any_after = any_after || row_word(wc) != 0;
-  // A window without kept blocks leaves the row's state alone; a row without any kept block at
-  // all writes its zeros in the launch of its last window.
-  if (!any_in && (any_before || any_after || win_end != last_word + 1)) return;
 
   // Q fragments (B operand of S^T = K Q^T) live in LDS, each lane's own 16 x 16 bytes: they are
   // re-read every tile, which frees 64 registers per lane for the K / V operand prefetch.
@@ -144,28 +141,12 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, in
       for (int r = 0; r < 16; ++r) oacc[dt][nt][r] = 0.0f;
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   const float cs = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(d)
-  const size_t unit_flat = (size_t)u.qh * g.n_qb + u.i;
-  f32x4* so = st_o + unit_flat * (32 * 64) + lane;          // [dt][nt][quarter][lane] 16-byte chunks
-  float* sml = st_ml + unit_flat * 256 + lane;               // [m nt0, m nt1, l nt0, l nt1][lane]
-  if (any_before) {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-          const f32x4 w = __builtin_nontemporal_load(&so[((dt * 2 + nt) * 4 + qd) * 64]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) oacc[dt][nt][4 * qd + e] = w[e];
-        }
-    m_run[0] = sml[0]; m_run[1] = sml[64]; l_run[0] = sml[128]; l_run[1] = sml[192];
-  }
 
-  int wc_it = win_begin;
-  uint64_t cur = row_word(win_begin);
+  int wc_it = 0;
+  uint64_t cur = row_word(0);
   auto next_block = [&]() -> int {
     while (cur == 0) {
-      if (++wc_it >= win_end) return -1;
+      if (++wc_it > last_word) return -1;
       cur = row_word(wc_it);
     }
     const int b = __builtin_ctzll(cur);
@@ -276,21 +257,6 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, in
     j_cur = j_next;
   }
 
-  if (any_after) {
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-          f32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = oacc[dt][nt][4 * qd + e];
-          __builtin_nontemporal_store(w, &so[((dt * 2 + nt) * 4 + qd) * 64]);
-        }
-    sml[0] = m_run[0]; sml[64] = m_run[1]; sml[128] = l_run[0]; sml[192] = l_run[1];
-    return;
-  }
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_run[nt] + swap_half(l_run[nt]);
@@ -310,34 +276,52 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(Geo g, int win_begin, in
   }
 }
 
+// Counting sort of the units of each KV head by kept-block count, descending:
+// order[kvh][rank] = unit id (block * group + head-in-group).  One workgroup per KV head.
+__global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t* __restrict__ row_counts,
+                                                           int32_t* __restrict__ order) {
+  __shared__ int bin[kMaskWordsMax * 64 + 2];
+  const int kvh = blockIdx.x, units = g.n_qb * g.group, nbins = g.n_kb + 1;
+  for (int b = threadIdx.x; b < nbins; b += blockDim.x) bin[b] = 0;
+  __syncthreads();
+  auto count_of = [&](int id) {
+    const int c = row_counts[(size_t)(kvh * g.group + id % g.group) * g.n_qb + id / g.group];
+    return min(max(c, 0), g.n_kb);
+  };
+  for (int id = threadIdx.x; id < units; id += blockDim.x) atomicAdd(&bin[count_of(id)], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {          // start offset of every bin, largest count first
+    int run = 0;
+    for (int b = nbins - 1; b >= 0; --b) { const int n = bin[b]; bin[b] = run; run += n; }
+  }
+  __syncthreads();
+  for (int id = threadIdx.x; id < units; id += blockDim.x)
+    order[(size_t)kvh * units + atomicAdd(&bin[count_of(id)], 1)] = id;
+}
+
 static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
-                            void* o, float* lse, void* ws, hipStream_t st) {
+                            const int32_t* row_counts, void* o, float* lse, void* ws, hipStream_t st) {
   const Geo g = make_geo(p);
   const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
   u32x4* kp = (u32x4*)ws;
   u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
+  int32_t* order = (int32_t*)((uint16_t*)ws + 2 * tile_elems);
   rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * g.n_kb)), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
                                                                               (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  const int tiles = (g.n_qb * g.group + 3) / 4;
-  f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
-  float* st_ml = (float*)st_o + (size_t)g.n_qh * g.n_qb * (128 * 64);
-  // The dense kernel sweeps every row in one launch: neighbouring rows read the same blocks at the same
-  // time anyway.  A sparse row keeps a scattered subset, so the sweep is cut into windows of key blocks
-  // small enough for the window's K', V' of one KV head to stay in its XCD's L2; the rows' accumulators
-  // are parked in the workspace between windows.
-  const char* e = getenv("SALE_WIN_WORDS");
-  const int win_words = mask ? (e ? atoi(e) : 2) : g.words;
-  for (int wb = 0; wb < g.words; wb += win_words) {
-    // units are dealt longest rows first: those that end before this window sit at the end of the grid
-    const int t_min = (wb * 64 * g.group) / 4;
-    const int nb = (tiles - t_min) * g.n_kvh;
-    if (nb <= 0) break;
-    attn_rows_kernel<<<dim3((unsigned)nb), dim3(256), 0, st>>>(g, wb, win_words, (const uint16_t*)q, (const bf16x8*)kp,
-                                                               (const bf16x8*)vp, mask, (uint16_t*)o, lse, st_o, st_ml);
-    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  const int units = g.n_qb * g.group;
+  if (mask) {
+    if (row_counts) {
+      order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
+      if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+    }
+    attn_rows_kernel<1><<<dim3((unsigned)(units * g.n_kvh)), dim3(64), 0, st>>>(
+        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask, row_counts ? order : nullptr, (uint16_t*)o, lse);
+  } else {
+    attn_rows_kernel<4><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
+        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, lse);
   }
-  return SALE_OK;
+  return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 
 }  // namespace sale
@@ -347,13 +331,12 @@ using namespace sale;
 extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
                                 const uint64_t* block_mask, const int32_t* row_counts, void* o, float* lse, void* ws,
                                 size_t ws_bytes, void* stream) {
-  (void)row_counts;
   if (!p || !q || !k || !v || !block_mask || !o) return SALE_ERR_NULL_ARG;
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
   if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, block_mask, o, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, lse, ws, (hipStream_t)stream);
 }
 
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
@@ -363,5 +346,5 @@ extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
   if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, nullptr, o, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, lse, ws, (hipStream_t)stream);
 }

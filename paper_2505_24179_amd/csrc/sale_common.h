@@ -24,7 +24,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 constexpr int kHeadDim = 128;   // d
 constexpr int kBlockQ = 64;     // b_q
 constexpr int kBlockK = 64;     // b_k
-constexpr int kMaskWordsMax = 64;            // mask words per row the attention kernel stages in LDS
+constexpr int kMaskWordsMax = 64;            // longest mask row, in 64-bit words
 constexpr int kMaxSeqLen = kMaskWordsMax * 64 * kBlockK;   // 262144 tokens
 
 // Flattened geometry handed to kernels.
@@ -71,19 +71,6 @@ __device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
   Unit u;
   u.kvh = block % g.n_kvh;
   const int t = tiles - 1 - block / g.n_kvh;
-  const int id = t * 4 + wave;
-  u.valid = id < units;
-  u.i = u.valid ? id / g.group : 0;
-  u.qh = u.kvh * g.group + (u.valid ? id % g.group : 0);
-  return u;
-}
-
-__device__ __forceinline__ Unit unit_of_kv_major(const Geo& g, int block, int wave) {
-  const int units = g.n_qb * g.group;
-  const int tiles = (units + 3) / 4;
-  Unit u;
-  u.kvh = block / tiles;
-  const int t = tiles - 1 - block % tiles;
   const int id = t * 4 + wave;
   u.valid = id < units;
   u.i = u.valid ? id / g.group : 0;
