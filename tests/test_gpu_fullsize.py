@@ -1,0 +1,92 @@
+"""GPU parity at the benchmark's full sizes (32K, 64K, 128K tokens, 32/8 heads),
+in the launch configuration bench.py times, on sampled (head, query block)
+units the oracle can compute one by one.  Query blocks are independent given
+all of K and V, so parity on a sampled block is exact parity for its rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sale_oracle as so
+from paper_2505_24179_amd import inputs
+from tests.parity_utils import check_output, compare_mask_row, words_to_bool
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sale():
+    from paper_2505_24179_amd import sale as mod
+    return mod
+
+
+def _sample_units(w, n_q, k, seed):
+    rng = np.random.default_rng(seed)
+    units = [(0, 0), (w.n_q_heads - 1, n_q - 1), (w.n_q_heads // 2, n_q - 1), (1, 4), (2, 5), (3, 63), (4, 64)]
+    while len(units) < k:
+        units.append((int(rng.integers(0, w.n_q_heads)), int(rng.integers(0, n_q))))
+    return units
+
+
+@pytest.mark.parametrize("name,n_units", [("llama31-8b-layer-32k", 14), ("llama31-8b-layer-64k", 12),
+                                          ("llama31-8b-layer-128k", 12)])
+def test_full_size_sampled_parity(sale, name, n_units):
+    w = inputs.WORKLOADS[name]
+    print(f"\n[{name}] generating inputs", flush=True)
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+    tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    mask, counts, m, l = sale.select(p, qd, kd, q4, k4, qs, ks, tau, want_stats=True)
+    ws = torch.empty(sale.workspace_bytes(p, sale.WS_SPARSE_ATTN), dtype=torch.uint8, device=dev)
+    o_sparse, _ = sale.sparse_attn(p, qd, kd, vd, mask, counts, ws=ws)
+    o_dense, lse_dense = sale.dense_attn(p, qd, kd, vd, want_lse=True, ws=ws)
+    torch.cuda.synchronize()
+    print(f"[{name}] GPU path done, density "
+          f"{int(counts.sum()) / (w.n_q_heads * p.n_q * (p.n_q + 1) // 2):.4f}", flush=True)
+
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    kq = {}
+    hard = soft = 0
+    worst_sparse = worst_dense = 0.0
+    for h, i in _sample_units(w, p.n_q, n_units, seed=w.seed & 0xFFFF):
+        g = h // w.group
+        if g not in kq:
+            kf = k[g].float().numpy()
+            kc, oks = so.quantize_blocks(kf[None], 64)
+            kq = {g: (kf, kc[0], oks[0], v[g].float().numpy())}
+            np.testing.assert_array_equal(k4[0, g].cpu().numpy(), so.pack_int4(kc[0]))
+            np.testing.assert_array_equal(ks[0, g].cpu().numpy().view(np.uint32), oks[0].view(np.uint32))
+        kf, kc, oks, vf = kq[g]
+        rs = slice(i * 64, (i + 1) * 64)
+        qf = q[h, rs].float().numpy()
+        qc, oqs = so.quantize_blocks(qf[None], 64)
+        # a1: codes and scale of the sampled query block
+        np.testing.assert_array_equal(q4[0, h, rs].cpu().numpy(), so.pack_int4(qc[0]))
+        assert qs[0, h, i].cpu().numpy().view(np.uint32) == oqs[0, 0].view(np.uint32)
+        # a3: integer products against 3 key-block ranges of this row
+        for jb in sorted({0, i // 2, max(0, i - 7)}):
+            je = min(jb + 8, i + 1)
+            got = sale.qk_int4_products(p, q4, k4, h, i, jb, je).cpu().numpy()
+            np.testing.assert_array_equal(got, so.int_products(qc[0], kc[jb * 64:je * 64]))
+        # a2, a4, a5: statistics and the mask row
+        row, margin, mthr, thr, om, ol = so.select_row(geo, i, qf, kf, qc[0], kc, float(oqs[0, 0]), oks, w.tau)
+        np.testing.assert_allclose(m[0, h, rs].cpu().numpy(), om, rtol=2e-6, atol=2e-6)
+        np.testing.assert_allclose(l[0, h, rs].cpu().numpy(), ol, rtol=2e-5)
+        got_row = words_to_bool(mask[0, h, i].cpu().numpy(), p.n_k)
+        a, b = compare_mask_row(got_row, row, margin, mthr)
+        hard += a; soft += b
+        assert int(counts[0, h, i]) == int(got_row.sum())
+        # a6, a7: outputs of the sampled rows (the oracle attends over the GPU's mask row)
+        ref_s, _ = so.attention_block(geo, i, qf, kf, vf, got_row)
+        ref_d, ref_lse = so.attention_block(geo, i, qf, kf, vf, so.dense_mask(geo)[i] if w.seq_len <= 32768
+                                            else np.arange(geo.n_k) <= i)
+        ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"sparse {name} h{h} i{i}")
+        md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"dense {name} h{h} i{i}")
+        np.testing.assert_allclose(lse_dense[0, h, rs].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+        worst_sparse, worst_dense = max(worst_sparse, ms), max(worst_dense, md)
+        print(f"[{name}] unit (h={h}, i={i}) kept {int(got_row.sum())}/{i + 1} ok", flush=True)
+    print(f"[{name}] borderline mask differences {soft}, max abs err sparse {worst_sparse:.3g} dense {worst_dense:.3g}")
+    assert hard == 0
+    assert soft <= 4
