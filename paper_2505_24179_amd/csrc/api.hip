@@ -47,7 +47,8 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
   const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
   switch (which_call) {
     case SALE_WS_SELECT:
-      return rows * sizeof(float);        // thr_r = ln(tau l~_r) + m~_r per query row
+      // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copies of Q~ and K~ (96 B per row)
+      return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96;
     case SALE_WS_SPARSE_ATTN:   // K and V copied once into MFMA fragment order
     case SALE_WS_DENSE_ATTN:
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +

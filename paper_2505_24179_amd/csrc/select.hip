@@ -9,10 +9,8 @@
 // in-lane max chain, the per-query threshold is a single register, and the
 // "any row of the block passes" reduction is the wave-wide compare mask.
 //
-// CDNA4 has no int4 MFMA.  The 4-bit codes are expanded on the fly to int8
-// holding 16*code (one AND / one shift+AND per four codes: the nibble simply
-// becomes the byte's high half), multiplied on the int8 MFMA with int32
-// accumulation, and the exact integer product is acc / 256.
+// CDNA4 has no int4 MFMA: the integer products run, exactly, on the FP6 MFMA
+// (see below).
 #include "sale_common.h"
 
 namespace sale {
@@ -101,111 +99,196 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
 }
 
 // ---------------------------------------------------------------------------
-// 4-bit estimate on the int8 MFMA
+// 4-bit estimate on the FP6 (E2M3) MFMA
 // ---------------------------------------------------------------------------
-// A lane's 16 packed bytes (32 codes) become the operands of two k-steps of
-// 16 int8 each.  Which channel lands in which k slot does not matter as long
-// as Q~ and K~ use the same expansion: the contraction sums over all of them.
-__device__ __forceinline__ void expand16(const u32x4 w, i32x4& s0, i32x4& s1) {
-  s0[0] = (int)((w[0] << 4) & 0xF0F0F0F0u); s0[1] = (int)(w[0] & 0xF0F0F0F0u);
-  s0[2] = (int)((w[1] << 4) & 0xF0F0F0F0u); s0[3] = (int)(w[1] & 0xF0F0F0F0u);
-  s1[0] = (int)((w[2] << 4) & 0xF0F0F0F0u); s1[1] = (int)(w[2] & 0xF0F0F0F0u);
-  s1[2] = (int)((w[3] << 4) & 0xF0F0F0F0u); s1[3] = (int)(w[3] & 0xF0F0F0F0u);
+// CDNA4 has no int4 MFMA.  Every integer in [-7, 7] is exactly representable in
+// FP6 E2M3 (1 sign, 2 exponent, 3 mantissa bits, bias 1: 1 = 0b001000, 2 =
+// 0b010000, 3 = 0b010100, 4 = 0b011000, 5 = 0b011010, 6 = 0b011100, 7 =
+// 0b011110), products are at most 49 and a 128-term sum at most 6272 < 2^24, so
+// v_mfma_f32_32x32x64_f8f6f4 with both operands in E2M3 and unit scales returns
+// the integer product EXACTLY in its fp32 accumulator (checked on hardware
+// against integer arithmetic, including all-(+-7) operands) at twice the int8
+// MFMA rate.  A pre-pass re-encodes the nibble codes once into MFMA operand
+// order ("X6"): per 64-row block 4 fragments f = 2*t + ks (rows 32t.., channels
+// 64ks..); lane l of a fragment owns row 32t + l%32, channels 64ks + 32(l/32) +
+// e, e = 0..31, as 32 six-bit codes = 6 dwords, stored as
+//   [block][f][lane] 16 bytes (dwords 0..3)  followed by  [block][f][lane] 8 bytes (dwords 4..5).
+constexpr int kX6BlockBytes = 4 * 64 * 24;   // 6144
+
+// E2M3 code of a 4-bit two's-complement nibble n (-7..7).
+__device__ __forceinline__ uint32_t e2m3_of_nibble(uint32_t n) {
+  const uint32_t sign = (n >> 3) & 1u;
+  const uint32_t mag = ((n ^ (0u - sign)) + sign) & 7u;          // |value|
+  return (sign << 5) | (((0xFEDCA840u >> (4u * mag)) & 0xFu) << 1);
 }
 
-// Rows row0 + 32*t + lane%32 (t = 0, 1) of a packed [rows][64-byte] matrix.
-__device__ __forceinline__ void load_frags(const uint8_t* __restrict__ base, size_t row0, int lane, i32x4 f[2][4]) {
-  const int c = lane & 31, h = lane >> 5;
+// 16 packed bytes (32 nibble codes, channel order) -> 32 six-bit codes in 6 dwords.
+__device__ __forceinline__ void pack_fp6(const u32x4 w, uint32_t out[6]) {
+  uint64_t acc = 0;
+  int bits = 0, o = 0;
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const uint8_t* row = base + (row0 + 32 * t + c) * 64 + 16 * h;
-#pragma unroll
-    for (int c16 = 0; c16 < 2; ++c16) {
-      const u32x4 w = *(const u32x4*)(row + 32 * c16);
-      expand16(w, f[t][2 * c16], f[t][2 * c16 + 1]);
+  for (int e = 0; e < 32; ++e) {
+    const uint32_t nib = (w[e >> 3] >> (4 * (e & 7))) & 0xFu;
+    acc |= (uint64_t)e2m3_of_nibble(nib) << bits;
+    bits += 6;
+    if (bits >= 32) {
+      out[o++] = (uint32_t)acc;
+      acc >>= 32;
+      bits -= 32;
     }
   }
 }
 
-// acc[mt][nt] = 256 * (K~ tile mt) (Q~ tile nt)^T, keys x queries.
-__device__ __forceinline__ void qk_tile(const i32x4 kf[2][4], const i32x4 qf[2][4], i32x16 acc[2][2]) {
+// One thread per (block, fragment, lane) of a nibble-packed [rows][64-byte] matrix.
+__global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict__ xa, uint8_t* __restrict__ ya,
+                                                       long blocks_a, const uint8_t* __restrict__ xb,
+                                                       uint8_t* __restrict__ yb) {
+  long blk = blockIdx.x;
+  const uint8_t* x = xa;
+  uint8_t* y = ya;
+  if (blk >= blocks_a) { blk -= blocks_a; x = xb; y = yb; }
+  const int f = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t = f >> 1, ks = f & 1;
+  const u32x4 w = *(const u32x4*)(x + ((size_t)blk * 64 + 32 * t + (lane & 31)) * 64 + 32 * ks + 16 * (lane >> 5));
+  uint32_t d[6];
+  pack_fp6(w, d);
+  uint8_t* yb_ = y + (size_t)blk * kX6BlockBytes;
+  u32x4 lo;
+  lo[0] = d[0]; lo[1] = d[1]; lo[2] = d[2]; lo[3] = d[3];
+  u32x2 hi;
+  hi[0] = d[4]; hi[1] = d[5];
+  *(u32x4*)(yb_ + (f * 64 + lane) * 16) = lo;
+  *(u32x2*)(yb_ + 4096 + (f * 64 + lane) * 8) = hi;
+}
+
+// The 4 operand fragments of block `blk` of an X6 array.
+__device__ __forceinline__ void load_x6(const uint8_t* __restrict__ base, size_t blk, int lane, i32x8 f[4]) {
+  const uint8_t* b = base + blk * kX6BlockBytes;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const u32x4 lo = *(const u32x4*)(b + (i * 64 + lane) * 16);
+    const u32x2 hi = *(const u32x2*)(b + 4096 + (i * 64 + lane) * 8);
+    f[i][0] = lo[0]; f[i][1] = lo[1]; f[i][2] = lo[2]; f[i][3] = lo[3];
+    f[i][4] = hi[0]; f[i][5] = hi[1]; f[i][6] = 0; f[i][7] = 0;
+  }
+}
+
+// acc[mt][nt] = (K~ tile mt) (Q~ tile nt)^T, keys x queries, exact integers held in fp32.
+__device__ __forceinline__ void qk_tile_fp6(const i32x8 kf[4], const i32x8 qf[4], f32x16 acc[2][2]) {
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      i32x16 a = {0};
+      f32x16 a = {0};
 #pragma unroll
-      for (int s = 0; s < 4; ++s) a = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf[mt][s], qf[nt][s], a, 0, 0, 0);
+      for (int ks = 0; ks < 2; ++ks)
+        a = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[2 * mt + ks], qf[2 * nt + ks], a, 2, 2, 0, 0, 0, 0);
       acc[mt][nt] = a;
     }
 }
 
-__global__ __launch_bounds__(256) void select_kernel(Geo g, const uint8_t* __restrict__ q4, const uint8_t* __restrict__ k4,
+// One wave scores HPW query heads of one GQA group at the same query block, so every K~ fragment it
+// loads feeds HPW x 2 MFMAs.  A workgroup is 4 such waves (consecutive head sets / query blocks of one
+// KV head); workgroups go round-robin over KV heads, longest rows first.
+// (At least 2 waves per SIMD caps the register file at 256 VGPRs, which lets the MFMA results land in
+// ordinary VGPRs instead of AGPRs that the max chain would have to copy out one by one.)
+template <int HPW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void select_kernel(Geo g, const uint8_t* __restrict__ q6, const uint8_t* __restrict__ k6,
                                                      const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                                                      const float* __restrict__ thr, uint64_t* __restrict__ mask,
                                                      int32_t* __restrict__ row_counts) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const Unit u = unit_of(g, blockIdx.x, wave);
-  if (!u.valid) return;
   const int c = lane & 31;
+  const int sets = g.group / HPW;                 // head sets per (KV head, query block)
+  const int units = g.n_qb * sets;
+  const int tiles = (units + 3) / 4;
+  const int kvh = blockIdx.x % g.n_kvh;
+  const int id = (tiles - 1 - blockIdx.x / g.n_kvh) * 4 + wave;
+  if (id >= units) return;
+  const int i = id / sets;
+  const int qh0 = kvh * g.group + (id % sets) * HPW;
 
-  i32x4 qf[2][4];
-  load_frags(q4 + (size_t)u.qh * g.seq * 64, (size_t)u.i * 64, lane, qf);
-  float th[2];
-  th[0] = thr[(size_t)u.qh * g.seq + u.i * 64 + c];
-  th[1] = thr[(size_t)u.qh * g.seq + u.i * 64 + 32 + c];
-  // dequantization factor of the block pair, without the key scale: s_q / sqrt(d) / 256
-  const float cq = q_scale[(size_t)u.qh * g.n_qb + u.i] * (0.08838834764831845f / 256.0f);
-  const float* ks = k_scale + (size_t)u.kvh * g.n_kb;
-  const uint8_t* kbase = k4 + (size_t)u.kvh * g.seq * 64;
-  uint64_t* mrow = mask + ((size_t)u.qh * g.n_qb + u.i) * g.words;
+  i32x8 qf[HPW][4];
+  float th[HPW][2], cq[HPW];
+#pragma unroll
+  for (int a = 0; a < HPW; ++a) {
+    load_x6(q6, (size_t)(qh0 + a) * g.n_qb + i, lane, qf[a]);
+    th[a][0] = thr[(size_t)(qh0 + a) * g.seq + i * 64 + c];
+    th[a][1] = thr[(size_t)(qh0 + a) * g.seq + i * 64 + 32 + c];
+    cq[a] = q_scale[(size_t)(qh0 + a) * g.n_qb + i] * 0.08838834764831845f;   // s_q / sqrt(d)
+  }
+  const float* ks = k_scale + (size_t)kvh * g.n_kb;
+  const size_t kblk0 = (size_t)kvh * g.n_kb;
 
-  const int j_last = u.i;
-  int count = 0;
+  const int j_last = i;
+  int count[HPW];
+#pragma unroll
+  for (int a = 0; a < HPW; ++a) count[a] = 0;
   for (int wc = 0; wc < g.words; ++wc) {
-    uint64_t word = 0;
+    uint64_t word[HPW];
+#pragma unroll
+    for (int a = 0; a < HPW; ++a) word[a] = 0;
     const int j_end = min(64, j_last + 1 - wc * 64);
     for (int jj = 0; jj < j_end; ++jj) {
       const int j = wc * 64 + jj;
-      bool keep;
       if (in_sink_local(g, j, j_last)) {
-        keep = true;
-      } else {
-        i32x4 kf[2][4];
-        load_frags(kbase, (size_t)j * 64, lane, kf);
-        i32x16 acc[2][2];
-        qk_tile(kf, qf, acc);
-        const float cj = cq * ks[j];
+#pragma unroll
+        for (int a = 0; a < HPW; ++a) word[a] |= 1ull << jj;
+        continue;
+      }
+      i32x8 kf[4];
+      load_x6(k6, kblk0 + j, lane, kf);
+      const float sk = ks[j];
+#pragma unroll
+      for (int a = 0; a < HPW; ++a) {
+        f32x16 acc[2][2];
+        qk_tile_fp6(kf, qf[a], acc);
+        const float cj = cq[a] * sk;
         bool pass = false;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-          int mx = acc[0][nt][0];
+          float mx = fmaxf(acc[0][nt][0], acc[1][nt][0]);
 #pragma unroll
-          for (int r = 1; r < 16; ++r) mx = max(mx, acc[0][nt][r]);
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = max(mx, acc[1][nt][r]);
-          pass = pass || ((float)mx * cj >= th[nt]);
+          for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, acc[0][nt][r]), acc[1][nt][r]);
+          pass = pass || (mx * cj >= th[a][nt]);
         }
-        keep = __ballot(pass) != 0ull;
+        word[a] |= (uint64_t)(__ballot(pass) != 0ull) << jj;
       }
-      word |= (uint64_t)keep << jj;
     }
-    if (lane == 0) mrow[wc] = word;
-    count += __popcll(word);
+#pragma unroll
+    for (int a = 0; a < HPW; ++a) {
+      if (lane == 0) mask[((size_t)(qh0 + a) * g.n_qb + i) * g.words + wc] = word[a];
+      count[a] += __popcll(word[a]);
+    }
   }
-  if (lane == 0) row_counts[(size_t)u.qh * g.n_qb + u.i] = count;
+#pragma unroll
+  for (int a = 0; a < HPW; ++a)
+    if (lane == 0) row_counts[(size_t)(qh0 + a) * g.n_qb + i] = count[a];
 }
 
-// Parity hook: the integer products themselves, one wave per key block.
+// Parity hook: the integer products themselves, one wave per key block, through the same
+// re-encoding and the same MFMA as the Selection-Pass.
 __global__ __launch_bounds__(64) void products_kernel(const uint8_t* __restrict__ q4_head, const uint8_t* __restrict__ k4_head,
                                                       int q_block, int k_begin, int n_kblocks, int32_t* __restrict__ out) {
   const int lane = threadIdx.x, c = lane & 31;
   const int jb = blockIdx.x;
-  i32x4 qf[2][4], kf[2][4];
-  load_frags(q4_head, (size_t)q_block * 64, lane, qf);
-  load_frags(k4_head, (size_t)(k_begin + jb) * 64, lane, kf);
-  i32x16 acc[2][2];
-  qk_tile(kf, qf, acc);
+  i32x8 qf[4], kf[4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    const int t = f >> 1, ks = f & 1;
+    const size_t off = (size_t)(32 * t + c) * 64 + 32 * ks + 16 * (lane >> 5);
+    uint32_t d[6];
+    pack_fp6(*(const u32x4*)(q4_head + (size_t)q_block * 4096 + off), d);
+#pragma unroll
+    for (int e = 0; e < 6; ++e) qf[f][e] = d[e];
+    qf[f][6] = 0; qf[f][7] = 0;
+    pack_fp6(*(const u32x4*)(k4_head + (size_t)(k_begin + jb) * 4096 + off), d);
+#pragma unroll
+    for (int e = 0; e < 6; ++e) kf[f][e] = d[e];
+    kf[f][6] = 0; kf[f][7] = 0;
+  }
+  f32x16 acc[2][2];
+  qk_tile_fp6(kf, qf, acc);
   const size_t ld = (size_t)n_kblocks * 64;
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
@@ -214,7 +297,7 @@ __global__ __launch_bounds__(64) void products_kernel(const uint8_t* __restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 32 * mt + mfma32_row(r, lane), qr = 32 * nt + c;
-        out[(size_t)qr * ld + jb * 64 + key] = acc[mt][nt][r] >> 8;
+        out[(size_t)qr * ld + jb * 64 + key] = (int32_t)acc[mt][nt][r];
       }
 }
 
@@ -235,11 +318,23 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
   const Geo g = make_geo(p);
   hipStream_t st = (hipStream_t)stream;
   const int tiles = (g.n_qb * g.group + 3) / 4;
-  const dim3 grid((unsigned)(tiles * g.n_kvh));
   float* thr = (float*)ws;
-  stats_kernel<<<grid, dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k, tau, tau_len, thr, m_out, l_out);
+  uint8_t* q6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
+  uint8_t* k6 = q6 + (size_t)g.n_qh * g.n_qb * kX6BlockBytes;
+  const long qblocks = (long)g.n_qh * g.n_qb, kblocks = (long)g.n_kvh * g.n_kb;
+  pack_fp6_kernel<<<dim3((unsigned)(qblocks + kblocks)), dim3(256), 0, st>>>(q4, q6, qblocks, k4, k6);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  select_kernel<<<grid, dim3(256), 0, st>>>(g, q4, k4, q_scale, k_scale, thr, block_mask, row_counts);
+  stats_kernel<<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k, tau,
+                                                                       tau_len, thr, m_out, l_out);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  if (g.group % 2 == 0) {
+    const int t2 = (g.n_qb * (g.group / 2) + 3) / 4;
+    select_kernel<2><<<dim3((unsigned)(t2 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr, block_mask,
+                                                                          row_counts);
+  } else {
+    select_kernel<1><<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr, block_mask,
+                                                                             row_counts);
+  }
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 
