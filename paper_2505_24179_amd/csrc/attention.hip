@@ -30,6 +30,8 @@
 //   decreasing kept-block count (a counting sort of row_counts).  In both,
 //   workgroups go round-robin over KV heads (blockIdx % n_kv_heads: one KV
 //   head per XCD / L2 when there are 8).
+#include <type_traits>
+
 #include "sale_common.h"
 
 namespace sale {
@@ -99,7 +101,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
                                                                const uint64_t* __restrict__ mask,
                                                                const int32_t* __restrict__ order,
                                                                uint16_t* __restrict__ o, float* __restrict__ lse) {
-  __shared__ bf16x8 sQ[WAVES][16][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 31, h = lane >> 5;
   const int units = g.n_qb * g.group;
@@ -123,15 +124,33 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     return mrow ? (mrow[wc] & causal) : causal;
   };
 
-  // Q fragments (B operand of S^T = K Q^T) live in LDS, each lane's own 16 x 16 bytes: they are
-  // re-read every tile, which frees 64 registers per lane for the K / V operand prefetch.
-  bf16x8* qs = &sQ[wave][0][lane];
+  // ---- operands -----------------------------------------------------------------------
+  // Q fragments (B operand of S^T = K Q^T), resident for the whole row.
+  bf16x8 qf[2][8];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qs[(nt * 8 + s) * 64] = *(const bf16x8*)(row + 16 * s);
+    for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
   }
+  const bf16x8* kt = kp + (size_t)u.kvh * g.n_kb * 1024 + lane;
+  const bf16x8* vt = vp + (size_t)u.kvh * g.n_kb * 1024 + lane;
+  // A block is processed as two half-tiles of 32 keys (mt = 0, 1).  K operands of half-tile mt:
+  // kf[mt][s]; V operands of half-tile mt: vf[mt][dt][s2] (k-steps s = 2*mt + s2 of the tile).
+  bf16x8 kf[2][8], vf[2][4][2];
+  auto load_k = [&](int j, int mt) __attribute__((always_inline)) {
+    const bf16x8* t = kt + (size_t)j * 1024 + mt * 512;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) kf[mt][s] = t[s * 64];
+  };
+  auto load_v = [&](int j, int mt) __attribute__((always_inline)) {
+    const bf16x8* t = vt + (size_t)j * 1024 + mt * 128;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) vf[mt][dt][s2] = t[(dt * 4 + s2) * 64];
+  };
+
   f32x16 oacc[4][2];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -154,69 +173,60 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     return wc_it * 64 + b;
   };
 
-  const bf16x8* kt = kp + (size_t)u.kvh * g.n_kb * 1024 + lane;
-  const bf16x8* vt = vp + (size_t)u.kvh * g.n_kb * 1024 + lane;
-  bf16x8 kf[2][8], vf[4][4];
-  auto load_k = [&](int j) {
-    const bf16x8* t = kt + (size_t)j * 1024;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-      for (int s = 0; s < 8; ++s) kf[mt][s] = t[(mt * 8 + s) * 64];
-  };
-  auto load_v = [&](int j) {
-    const bf16x8* t = vt + (size_t)j * 1024;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) vf[dt][s] = t[(dt * 4 + s) * 64];
-  };
+  // ---- pipeline stages ----------------------------------------------------------------
+  // Half-tile score accumulators S[mt][nt] (keys 32mt.. x queries 32nt..) and the bf16 P^T operands
+  // P[mt][nt][s2] made from them.  The MFMA stream and the softmax VALU stream of DIFFERENT half-tiles
+  // are written side by side so that they overlap inside one wave:
+  //   stage A: O += V^T P^T of the previous block's half 1   ||  row max of S[0], rescale test
+  //   stage B: S[1] = K Q^T of this block's half 1            ||  P[0] = exp2(S[0] - max), row sums
+  //   stage C: O += V^T P^T of this block's half 0            ||  row max of S[1], rescale test
+  //   stage D: S[0] = K Q^T of the NEXT block's half 0        ||  P[1] = exp2(S[1] - max), row sums
+  f32x16 S[2][2];
+  bf16x8 P[2][2][2];
 
-  int j_cur = next_block();
-  if (j_cur >= 0) { load_k(j_cur); load_v(j_cur); }
-  while (j_cur >= 0) {
-    const int j_next = next_block();
-    const int j_load = j_next >= 0 ? j_next : j_cur;
-
-    f32x16 sacc[2][2];
+  auto qk_half = [&](int mt) __attribute__((always_inline)) {                       // S[mt][*] = K(half mt) Q^T
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[mt][nt][r] = 0.0f;
-    int q_off = 0;
-    asm volatile("" : "+v"(q_off));   // opaque: keeps the Q reads inside the loop (they would be hoisted back into registers)
-    const bf16x8* qt = qs + q_off;
+      for (int r = 0; r < 16; ++r) S[mt][nt][r] = 0.0f;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const bf16x8 q0 = qt[s * 64], q1 = qt[(8 + s) * 64];
-#pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        sacc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], q0, sacc[mt][0], 0, 0, 0);
-        sacc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], q1, sacc[mt][1], 0, 0, 0);
-      }
+      S[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[0][s], S[mt][0], 0, 0, 0);
+      S[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[1][s], S[mt][1], 0, 0, 0);
     }
-    load_k(j_load);
-
-    const bool diag = j_cur == u.i;
-    bf16x8 pf[2][4];
+  };
+  auto pv_half = [&](int mt) __attribute__((always_inline)) {                       // O^T += V^T(half mt) P^T(half mt)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        oacc[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt][dt][s2], P[mt][0][s2], oacc[dt][0], 0, 0, 0);
+        oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt][dt][s2], P[mt][1][s2], oacc[dt][1], 0, 0, 0);
+      }
+  };
+  // Row maxima of half-tile mt (after causal masking on the diagonal block): mx[nt].
+  float mx[2];
+  auto max_half = [&](int mt, auto diag) __attribute__((always_inline)) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      if (diag) {
+      if constexpr (decltype(diag)::value) {
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) sacc[mt][nt][r] = -INFINITY;
+        for (int r = 0; r < 16; ++r)
+          if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
       }
-      float mx = fmaxf(sacc[0][nt][0], sacc[1][nt][0]);
+      float v = fmaxf(S[mt][nt][0], S[mt][nt][1]);
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, sacc[0][nt][r]), sacc[1][nt][r]);
-      mx = fmaxf(mx, swap_half(mx));
-      // Rescale only when some row's maximum grew (exact: otherwise the factor is 1).
-      if (__builtin_amdgcn_ballot_w64(mx > m_run[nt]) != 0ull) {
-        const float m_new = fmaxf(m_run[nt], mx);        // finite: key 0 of a kept block is visible to every row
+      for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[mt][nt][r]), S[mt][nt][r + 1]);
+      mx[nt] = max_with_other_half(v);
+    }
+  };
+  // Lazy rescale: O and l are rescaled only when some row's maximum grew (exact: otherwise the factor
+  // is 1).  Rows of the diagonal block that see no key of a half keep their (finite) maximum.
+  auto rescale = [&]() __attribute__((always_inline)) {
+    if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] || mx[1] > m_run[1]) != 0ull) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const float m_new = fmaxf(m_run[nt], mx[nt]);
         const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
         l_run[nt] *= alpha;
         m_run[nt] = m_new;
@@ -225,36 +235,96 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
       }
-      const float mb = m_run[nt] * cs;
-      bf16x2 ones;
-      ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
-      float sum = l_run[nt];
-      // P^T as the B operand of O^T = V^T P^T: k-step s takes registers 8*(s%2).. of tile s/2
+    }
+  };
+  // Interleave hint for the instruction scheduler: n times {1 MFMA, `valu` VALU, `vmem` loads}.
+#define SALE_PIPE(n, valu, vmem)                                        \
+  _Pragma("unroll") for (int i_ = 0; i_ < (n); ++i_) {                   \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   \
+    if ((valu) > 0) __builtin_amdgcn_sched_group_barrier(0x002, (valu), 0); \
+    if ((vmem) > 0) __builtin_amdgcn_sched_group_barrier(0x020, (vmem), 0); \
+  }
+  auto exp_half = [&](int mt) __attribute__((always_inline)) {                      // P[mt] = exp2(S[mt] * cs - m * cs), l += row sums
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
+    for (int nt = 0; nt < 2; ++nt) {
+      const float mb = m_run[nt] * cs;
+      float sum = l_run[nt];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
         u32x4 packed;
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
-          const int r = 8 * (s & 1) + 2 * e2;
+          const int r = 8 * s2 + 2 * e2;
           bf16x2 pk;
-          pk[0] = (__bf16)__builtin_amdgcn_exp2f(sacc[s >> 1][nt][r] * cs - mb);
-          pk[1] = (__bf16)__builtin_amdgcn_exp2f(sacc[s >> 1][nt][r + 1] * cs - mb);
+          pk[0] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r] * cs - mb);
+          pk[1] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r + 1] * cs - mb);
           sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);   // row sum of the rounded P
           packed[e2] = __builtin_bit_cast(unsigned, pk);
         }
-        pf[nt][s] = __builtin_bit_cast(bf16x8, packed);
+        P[mt][nt][s2] = __builtin_bit_cast(bf16x8, packed);
       }
       l_run[nt] = sum;
     }
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-          oacc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt][s], pf[nt][s], oacc[dt][nt], 0, 0, 0);
-    load_v(j_load);
-    j_cur = j_next;
+  };
+
+  // One kept block j.  first: no previous block whose half 1 is still to be multiplied.  last: no
+  // next block (j_next is then unused).  diag: j is the diagonal block (always the last of a row).
+  // Every load and MFMA of a variant is unconditional, so the compiler can count outstanding loads
+  // exactly and never has to drain the queue.
+  auto block_step = [&](int j, int j_next, auto first, auto last, auto diag) __attribute__((always_inline)) {
+    constexpr bool kLast = decltype(last)::value;
+    // stage A
+    if constexpr (!decltype(first)::value) pv_half(1);
+    max_half(0, diag);
+    load_v(j, 1);
+    if constexpr (!decltype(first)::value) { SALE_PIPE(16, 2, 1) }
+    rescale();
+    // stage B
+    qk_half(1);
+    exp_half(0);
+    // stage C
+    pv_half(0);
+    max_half(1, diag);
+    if constexpr (!kLast) { load_k(j_next, 1); load_v(j_next, 0); }
+    SALE_PIPE(16, 6, 0)
+    SALE_PIPE(16, 2, 1)
+    rescale();
+    // stage D (kf[0] of the next block was requested before stage A)
+    if constexpr (!kLast) qk_half(0);
+    exp_half(1);
+    if constexpr (!kLast) { SALE_PIPE(16, 6, 0) }
+  };
+  const auto T = std::true_type{};
+  const auto F = std::false_type{};
+
+  int j_cur = next_block();
+  if (j_cur >= 0) {
+    load_k(j_cur, 0);
+    load_k(j_cur, 1);
+    load_v(j_cur, 0);
+    qk_half(0);
+    int j_next = next_block();
+    if (j_next < 0) {
+      if (j_cur == u.i) block_step(j_cur, 0, T, T, T); else block_step(j_cur, 0, T, T, F);
+    } else {
+      // the list is read one block ahead of the loads so that no control flow separates the stages
+      load_k(j_next, 0);
+      int j_after = next_block();
+      block_step(j_cur, j_next, T, F, F);
+      j_cur = j_next;
+      j_next = j_after;
+      while (j_next >= 0) {
+        load_k(j_next, 0);
+        j_after = next_block();
+        block_step(j_cur, j_next, F, F, F);
+        j_cur = j_next;
+        j_next = j_after;
+      }
+      if (j_cur == u.i) block_step(j_cur, 0, F, T, T); else block_step(j_cur, 0, F, T, F);
+    }
+    pv_half(1);
   }
 
 #pragma unroll

@@ -53,6 +53,14 @@ __device__ __forceinline__ int mfma32_row(int r, int lane) { return 8 * (r >> 2)
 // Value held by the other half of the wave (lane ^ 32).
 __device__ __forceinline__ float swap_half(float x) { return __shfl_xor(x, 32, 64); }
 
+// max(x, x of lane ^ 32) without going through LDS: v_permlane32_swap leaves the lower half's
+// values in both halves of one result and the upper half's in the other.
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
 // Unit = (flattened query head, 64-row query block): the work of one wave.
 // Units of one KV head are numbered block-major, head-in-group minor, so the
 // four waves of a workgroup share their K (and V) rows.  Workgroups are dealt

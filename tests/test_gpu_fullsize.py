@@ -8,7 +8,7 @@ import torch
 
 from oracle import sale_oracle as so
 from paper_2505_24179_amd import inputs
-from tests.parity_utils import check_output, compare_mask_row, words_to_bool
+from tests.parity_utils import LSE_ATOL, check_output, compare_mask_row, words_to_bool
 
 pytestmark = pytest.mark.gpu
 
@@ -84,7 +84,7 @@ def test_full_size_sampled_parity(sale, name, n_units):
                                             else np.arange(geo.n_k) <= i)
         ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"sparse {name} h{h} i{i}")
         md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"dense {name} h{h} i{i}")
-        np.testing.assert_allclose(lse_dense[0, h, rs].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+        np.testing.assert_allclose(lse_dense[0, h, rs].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
         worst_sparse, worst_dense = max(worst_sparse, ms), max(worst_dense, md)
         print(f"[{name}] unit (h={h}, i={i}) kept {int(got_row.sum())}/{i + 1} ok", flush=True)
     print(f"[{name}] borderline mask differences {soft}, max abs err sparse {worst_sparse:.3g} dense {worst_dense:.3g}")

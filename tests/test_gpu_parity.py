@@ -13,7 +13,7 @@ import torch
 
 from oracle import sale_oracle as so
 from paper_2505_24179_amd import inputs
-from tests.parity_utils import (check_output, compare_mask_row, f32, oracle_quantize, words_to_bool)
+from tests.parity_utils import (LSE_ATOL, check_output, compare_mask_row, f32, oracle_quantize, words_to_bool)
 
 pytestmark = pytest.mark.gpu
 
@@ -181,7 +181,7 @@ def test_dense_attention_matches_oracle(case, sale):
     geo = so.Geometry(w.seq_len, w.head_dim)
     ref, ref_lse = _oracle_attention(w, q, k, v, [so.dense_mask(geo)] * w.n_q_heads)
     mx, mean = check_output(f32(o[0]), ref, f"dense {w.name}")
-    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
     print(f"[{w.name}] dense max abs {mx:.3g} mean abs {mean:.3g}")
 
 
@@ -197,7 +197,7 @@ def test_sparse_attention_matches_oracle_on_selected_mask(case, sale):
     got = words_to_bool(mask[0].cpu().numpy(), p.n_k)
     ref, ref_lse = _oracle_attention(w, q, k, v, got)
     mx, mean = check_output(f32(o[0]), ref, f"sparse {w.name}")
-    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=1e-4, atol=1e-4)
+    np.testing.assert_allclose(lse[0].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
     print(f"[{w.name}] sparse max abs {mx:.3g} mean abs {mean:.3g}")
 
 
