@@ -10,7 +10,7 @@
  * --------------------------------
  * - Every tensor pointer is a DEVICE pointer owned by the caller; the library
  *   never allocates or frees memory.  Scratch comes from a caller-provided
- *   workspace whose size sale_workspace_bytes() reports.
+ *   workspace (16-byte aligned) whose size sale_workspace_bytes() reports.
  * - Calls are asynchronous on the given hipStream_t (passed as void*; NULL =
  *   the default stream), never synchronise and keep no global state.
  * - All tensors are contiguous, row-major, last dimension fastest:
@@ -43,7 +43,7 @@ typedef enum sale_status {
   SALE_ERR_NULL_ARG = -1,     /* a required pointer is NULL                       */
   SALE_ERR_BAD_SHAPE = -2,    /* non-positive size, N not a multiple of the block */
   SALE_ERR_UNSUPPORTED = -3,  /* valid but not implemented geometry / flag        */
-  SALE_ERR_WORKSPACE = -4,    /* workspace NULL or smaller than required          */
+  SALE_ERR_WORKSPACE = -4,    /* workspace NULL, misaligned or smaller than required */
   SALE_ERR_HIP = -5           /* a HIP runtime call or kernel launch failed       */
 } sale_status;
 

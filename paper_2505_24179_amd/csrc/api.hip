@@ -49,10 +49,12 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
     case SALE_WS_SELECT:
       // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copies of Q~ and K~ (96 B per row)
       return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96;
-    case SALE_WS_SPARSE_ATTN:   // K and V copied once into MFMA fragment order
+    case SALE_WS_SPARSE_ATTN:
     case SALE_WS_DENSE_ATTN:
+      // K and V copied once into MFMA fragment order, parked row state (fp32 O^T accumulators and
+      // max / sum per lane: 33 KB per 64-row block) and the order in which rows are issued
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
-             (which_call == SALE_WS_SPARSE_ATTN ? (rows / kBlockQ) * sizeof(int32_t) : 0);   // unit order
+             (rows / kBlockQ) * (sizeof(int32_t) + 2048 * 16 + 256 * 4);
     default:
       return 0;
   }

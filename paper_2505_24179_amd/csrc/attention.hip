@@ -30,6 +30,7 @@
 //   decreasing kept-block count (a counting sort of row_counts).  In both,
 //   workgroups go round-robin over KV heads (blockIdx % n_kv_heads: one KV
 //   head per XCD / L2 when there are 8).
+#include <stdlib.h>
 #include <type_traits>
 
 #include "sale_common.h"
@@ -93,6 +94,18 @@ __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16
   }
 }
 
+// Which rows a launch handles and which part of them.  Rows whose kept-block count lies in
+// [count_min, count_max] take part (counts == nullptr: all rows).  win_word < 0: the whole row in one go.
+// win_word >= 0: only the key blocks of that 64-block mask word; a row then resumes from the state
+// (fp32 O^T accumulators, running max and sum, exactly the register contents) that the launch of the
+// previous word parked in the workspace, and parks it again unless this word holds its diagonal block.
+struct RowFilter {
+  const int32_t* counts;
+  int count_min, count_max;
+  int win_word;    // first mask word of the window, or < 0
+  int win_words;   // words per window
+};
+
 // order: optional [kv head][rank] -> unit id within the KV head (block * group + head-in-group).
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
@@ -100,7 +113,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
                                                                const bf16x8* __restrict__ vp,
                                                                const uint64_t* __restrict__ mask,
                                                                const int32_t* __restrict__ order,
-                                                               uint16_t* __restrict__ o, float* __restrict__ lse) {
+                                                               uint16_t* __restrict__ o, float* __restrict__ lse,
+                                                               RowFilter flt, f32x4* __restrict__ st_o,
+                                                               float* __restrict__ st_ml) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane & 31, h = lane >> 5;
   const int units = g.n_qb * g.group;
@@ -114,10 +129,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     u.qh = u.kvh * g.group + id % g.group;
   }
   if (!u.valid) return;
+  const size_t unit_flat = (size_t)u.qh * g.n_qb + u.i;
+  if (flt.counts) {
+    const int cnt = flt.counts[unit_flat];
+    if (cnt < flt.count_min || cnt > flt.count_max) return;
+  }
 
   // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
   const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
   const int last_word = u.i >> 6;
+  if (flt.win_word > last_word) return;
+  const int word_lo = flt.win_word >= 0 ? flt.win_word : 0;
+  const int word_hi = flt.win_word >= 0 ? min(flt.win_word + flt.win_words - 1, last_word) : last_word;
+  const bool resume = flt.win_word > 0, park = flt.win_word >= 0 && word_hi < last_word;
   auto row_word = [&](int wc) -> uint64_t {
     const int lo = wc * 64;
     const uint64_t causal = u.i >= lo + 63 ? ~0ull : ((2ull << (u.i - lo)) - 1ull);
@@ -161,11 +185,26 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
   const float cs = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(d)
 
-  int wc_it = 0;
-  uint64_t cur = row_word(0);
+  if (resume) {
+    const f32x4* so = st_o + unit_flat * 2048 + lane;       // [dt][nt][quarter][lane] 16-byte chunks
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          const f32x4 w = so[((dt * 2 + nt) * 4 + qd) * 64];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) oacc[dt][nt][4 * qd + e] = w[e];
+        }
+    const float* sml = st_ml + unit_flat * 256 + lane;       // [m nt0, m nt1, l nt0, l nt1][lane]
+    m_run[0] = sml[0]; m_run[1] = sml[64]; l_run[0] = sml[128]; l_run[1] = sml[192];
+  }
+  int wc_it = word_lo;
+  uint64_t cur = row_word(word_lo);
   auto next_block = [&]() -> int {
     while (cur == 0) {
-      if (++wc_it > last_word) return -1;
+      if (++wc_it > word_hi) return -1;
       cur = row_word(wc_it);
     }
     const int b = __builtin_ctzll(cur);
@@ -327,6 +366,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     pv_half(1);
   }
 
+  if (park) {
+    f32x4* so = st_o + unit_flat * 2048 + lane;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+          f32x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = oacc[dt][nt][4 * qd + e];
+          so[((dt * 2 + nt) * 4 + qd) * 64] = w;
+        }
+    float* sml = st_ml + unit_flat * 256 + lane;
+    sml[0] = m_run[0]; sml[64] = m_run[1]; sml[128] = l_run[0]; sml[192] = l_run[1];
+    return;
+  }
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_run[nt] + swap_half(l_run[nt]);
@@ -369,27 +425,58 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
     order[(size_t)kvh * units + atomicAdd(&bin[count_of(id)], 1)] = id;
 }
 
+constexpr int kLongRow = 192;   // rows keeping more blocks than this are swept word by word
+
 static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
                             const int32_t* row_counts, void* o, float* lse, void* ws, hipStream_t st) {
   const Geo g = make_geo(p);
   const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
   u32x4* kp = (u32x4*)ws;
   u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
-  int32_t* order = (int32_t*)((uint16_t*)ws + 2 * tile_elems);
+  // workspace: K' | V' | parked O^T state (32 KB per row block) | parked max / sum (1 KB) | unit order (i32)
+  const size_t n_units = (size_t)g.n_qh * g.n_qb;
+  f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
+  float* st_ml = (float*)(st_o + n_units * 2048);
+  int32_t* order = (int32_t*)(st_ml + n_units * 256);
   rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * g.n_kb)), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
                                                                               (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const int units = g.n_qb * g.group;
+  const RowFilter all = {nullptr, 0, 0, -1, 0};
   if (mask) {
-    if (row_counts) {
+    const dim3 grid((unsigned)(units * g.n_kvh));
+    if (!row_counts || g.words == 1) {
+      if (row_counts) {
+        order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
+        if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+      }
+      attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
+                                                    row_counts ? order : nullptr, (uint16_t*)o, lse, all, nullptr,
+                                                    nullptr);
+    } else {
+      // Long rows (more than kLongRow kept blocks) carry most of the work and keep scattered blocks over the
+      // whole sequence: swept independently they miss L2 on most loads.  They are processed one 64-block
+      // mask word at a time, all rows together, so that the K', V' of the word (2 MB per KV head) stay in
+      // the L2 of the XCD that owns the KV head; their accumulators wait in the workspace in between.
+      // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
       order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
       if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+      const char* e = getenv("SALE_WIN_WORDS");
+      const int ww = e ? atoi(e) : 1;
+      for (int w = 0; w < g.words; w += ww) {
+        const RowFilter lng = {row_counts, kLongRow + 1, 0x7FFFFFFF, w, ww};
+        attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp,
+                                                      mask, order, (uint16_t*)o, lse, lng, st_o, st_ml);
+        if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+      }
+      const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow, -1, 0};
+      attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
+                                                    order, (uint16_t*)o, lse, shrt, nullptr, nullptr);
     }
-    attn_rows_kernel<1><<<dim3((unsigned)(units * g.n_kvh)), dim3(64), 0, st>>>(
-        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask, row_counts ? order : nullptr, (uint16_t*)o, lse);
   } else {
     attn_rows_kernel<4><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
-        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, lse);
+        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, lse, all, nullptr,
+        nullptr);
   }
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
@@ -405,7 +492,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
-  if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
   return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, lse, ws, (hipStream_t)stream);
 }
 
@@ -415,6 +502,6 @@ extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
-  if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
   return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, lse, ws, (hipStream_t)stream);
 }

@@ -314,7 +314,7 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
   if (rc != SALE_OK) return rc;
   if (tau_len != 1 && tau_len != p->n_q_heads) return SALE_ERR_BAD_SHAPE;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SELECT);
-  if (!ws || ws_bytes < need) return SALE_ERR_WORKSPACE;
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
   const Geo g = make_geo(p);
   hipStream_t st = (hipStream_t)stream;
   const int tiles = (g.n_qb * g.group + 3) / 4;

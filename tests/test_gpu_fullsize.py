@@ -21,16 +21,22 @@ def sale():
 
 def _sample_units(w, n_q, k, seed):
     rng = np.random.default_rng(seed)
-    units = [(0, 0), (w.n_q_heads - 1, n_q - 1), (w.n_q_heads // 2, n_q - 1), (1, 4), (2, 5), (3, 63), (4, 64)]
+    units = [(0, 0), (w.n_q_heads - 1, n_q - 1), (w.n_q_heads // 2, n_q - 1), (1, 4), (2, 5), (3, 63), (4, 64),
+             (5, n_q - 2), (6, 193), (7, 255)]
     while len(units) < k:
         units.append((int(rng.integers(0, w.n_q_heads)), int(rng.integers(0, n_q))))
     return units
 
 
-@pytest.mark.parametrize("name,n_units", [("llama31-8b-layer-32k", 14), ("llama31-8b-layer-64k", 12),
-                                          ("llama31-8b-layer-128k", 12)])
+# A mid-size case with a low threshold: many rows keep more than 192 blocks over 4 mask words, which
+# is the path that sweeps long rows word by word with parked accumulators.
+LONG_ROWS_16K = inputs.Workload("gqa4-16k-long-rows", 16384, 8, 2, seed=0x5A1E0010, tau=0.0005)
+
+
+@pytest.mark.parametrize("name,n_units", [("gqa4-16k-long-rows", 24), ("llama31-8b-layer-32k", 14),
+                                          ("llama31-8b-layer-64k", 12), ("llama31-8b-layer-128k", 12)])
 def test_full_size_sampled_parity(sale, name, n_units):
-    w = inputs.WORKLOADS[name]
+    w = LONG_ROWS_16K if name == LONG_ROWS_16K.name else inputs.WORKLOADS[name]
     print(f"\n[{name}] generating inputs", flush=True)
     q, k, v = inputs.make_inputs(w)
     p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
