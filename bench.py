@@ -154,7 +154,7 @@ def main() -> int:
         "quantize": {"bound": "hbm", "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "ms": quant_ms},
         "select": {"bound": "mfma", "achieved": middle_pairs * 2.0 * 64 * 64 * 128 / (select_ms * 1e-3) / 1e12,
-                   "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "ms": select_ms},
+                   "peak": PEAK_FP6_TFLOPS, "unit": "TFLOP/s", "ms": select_ms},
         "sparse_attn": {"bound": "mfma", "achieved": kept_pairs * flop_pair / (sparse_ms * 1e-3) / 1e12,
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "ms": sparse_ms},
     }
@@ -167,6 +167,14 @@ def main() -> int:
     roof = dict(kernels[dominant])
     roof.pop("ms")
     roof.update({"kernel": dominant, "traffic": None})
+    # HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (committed summary)
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(tfile) and args.tau is None:
+        with open(tfile) as f:
+            t = json.load(f).get(dominant)
+        if t:
+            roof["traffic"] = {"read_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
+                               "source": os.path.relpath(tfile, ROOT)}
 
     out = {
         "metric": "sparse prefill attn ms + speedup vs own dense kernel at 128K; select overhead %",
