@@ -175,16 +175,19 @@ __device__ __forceinline__ void load_x6(const uint8_t* __restrict__ base, size_t
 
 // acc[mt][nt] = (K~ tile mt) (Q~ tile nt)^T, keys x queries, exact integers held in fp32.
 __device__ __forceinline__ void qk_tile_fp6(const i32x8 kf[4], const i32x8 qf[4], f32x16 acc[2][2]) {
+  // the two k-steps of a tile depend on each other: issue the four tiles' first steps, then their second
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      f32x16 a = {0};
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-        a = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[2 * mt + ks], qf[2 * nt + ks], a, 2, 2, 0, 0, 0, 0);
-      acc[mt][nt] = a;
+      const f32x16 z = {0};
+      acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[2 * mt], qf[2 * nt], z, 2, 2, 0, 0, 0, 0);
     }
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+      acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kf[2 * mt + 1], qf[2 * nt + 1], acc[mt][nt], 2, 2, 0, 0, 0, 0);
 }
 
 // One wave scores HPW query heads of one GQA group at the same query block, so every K~ fragment it

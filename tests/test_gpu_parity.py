@@ -251,3 +251,40 @@ def test_batch_two_equals_two_single_batches(sale):
         assert torch.equal(mk[0], mask[b]) and torch.equal(ct[0], counts[b])
         ob, _ = sale.sparse_attn(p1, qq, kk, vv, mk, ct)
         assert torch.equal(ob[0], o[b])
+
+
+def test_repeat_runs_are_bit_identical(sale):
+    """The path has no run-to-run freedom in its results (the row order of the sparse kernel is not
+    deterministic, the rows are independent)."""
+    w = CASES["gqa8-4k"]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    qd, kd, vd = _dev(q, k, v)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    outs = []
+    for _ in range(3):
+        q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+        mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+        o, lse = sale.sparse_attn(p, qd, kd, vd, mask, counts, want_lse=True)
+        od, _ = sale.dense_attn(p, qd, kd, vd)
+        outs.append((q4, k4, qs, ks, mask, counts, o, lse, od))
+    torch.cuda.synchronize()
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
+
+
+def test_misaligned_or_small_workspace_is_rejected(sale):
+    w = CASES["one-block"]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, 1, 1, 64)
+    qd, kd, vd = _dev(q, k, v)
+    big = torch.empty(sale.workspace_bytes(p, sale.WS_DENSE_ATTN) + 64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sale.SaleError) as e:
+        sale.dense_attn(p, qd, kd, vd, ws=big[8:])          # 8-byte offset: not 16-byte aligned
+    assert e.value.status == -4
+    with pytest.raises(sale.SaleError) as e:
+        sale.dense_attn(p, qd, kd, vd, ws=big[:1024])
+    assert e.value.status == -4
+    o, _ = sale.dense_attn(p, qd, kd, vd, ws=big[16:])       # aligned and large enough: fine
+    assert torch.isfinite(o.float()).all()
