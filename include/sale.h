@@ -12,7 +12,8 @@
  *   never allocates or frees memory.  Scratch comes from a caller-provided
  *   workspace (16-byte aligned) whose size sale_workspace_bytes() reports.
  * - Calls are asynchronous on the given hipStream_t (passed as void*; NULL =
- *   the default stream), never synchronise and keep no global state.
+ *   the default stream), never synchronise (sale_calibrate_tau excepted) and
+ *   keep no global state.
  * - All tensors are contiguous, row-major, last dimension fastest:
  *     Q, O : bf16 [batch][n_q_heads ][seq_len][head_dim]
  *     K, V : bf16 [batch][n_kv_heads][seq_len][head_dim]
@@ -71,6 +72,7 @@ typedef struct sale_params {
 #define SALE_WS_SELECT 1
 #define SALE_WS_SPARSE_ATTN 2
 #define SALE_WS_DENSE_ATTN 3
+#define SALE_WS_CALIBRATE 4
 
 /* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
  * parameters are invalid). */
@@ -165,6 +167,25 @@ int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, const uint8
                           int32_t q_head, int32_t q_block,
                           int32_t k_block_begin, int32_t k_block_end,
                           int32_t* out, void* stream);
+
+/*
+ * Per-head threshold calibration (Sec. 3.3).  For every query head, starting from tau0 (the paper uses
+ * 0.008), tau is halved until Err(tau) = ||O - O~||_1 / N < theta, where O is full causal attention and
+ * O~ the SALE output (Selection-Pass with that tau + Computation-Pass) of the same inputs, both taken in
+ * fp32 before the output rounding; at most max_halvings halvings (0..64).  With batch > 1 the batch
+ * entries are calibration samples and every one of them has to satisfy the bound (Appendix C).
+ * This is an offline procedure: unlike the other calls it SYNCHRONISES `stream` (once per round) and
+ * uses host memory for Hq-sized bookkeeping.
+ *
+ *   tau_out      out: fp32 [n_q_heads] (device), the calibrated thresholds
+ *   err_out      out: optional fp32 [n_q_heads] (device), Err at the returned tau (worst sample)
+ *   halvings_out out: optional int32 [n_q_heads] (device), number of halvings taken
+ *   ws              : workspace of sale_workspace_bytes(p, SALE_WS_CALIBRATE) bytes, 256-byte aligned
+ */
+int sale_calibrate_tau(const sale_params_t* p, const void* q, const void* k, const void* v,
+                       float tau0, float theta, int32_t max_halvings,
+                       float* tau_out, float* err_out, int32_t* halvings_out,
+                       void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -274,3 +274,27 @@ def dense_mask(geo: Geometry) -> np.ndarray:
 def is_borderline(margin, thr_scale, rel: float = 1e-5):
     """Decisions whose margin lies within rel * max(1, |thr|) of zero."""
     return np.abs(margin) <= rel * np.maximum(1.0, np.abs(thr_scale))
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.3: per-head threshold calibration
+# --------------------------------------------------------------------------
+def calibration_error(o_full: np.ndarray, o_sale: np.ndarray) -> float:
+    """Err = ||O - O~||_1 / N for one head (O: N x d)."""
+    o_full = np.asarray(o_full, dtype=np.float64)
+    return float(np.abs(o_full - np.asarray(o_sale, dtype=np.float64)).sum() / o_full.shape[0])
+
+
+def calibrate_head(geo: Geometry, q, k, v, q_codes, k_codes, s_q, s_k, tau0: float, theta: float, max_halvings: int):
+    """Sec. 3.3 for one head: start at tau0 and halve tau until Err(tau) < theta (at most max_halvings
+    times).  Returns (tau, halvings, [Err at every tau tried])."""
+    o_full, _ = attention_head(geo, q, k, v, dense_mask(geo))
+    tau, errs = float(tau0), []
+    for n in range(max_halvings + 1):
+        mask, *_ = select_head(geo, q, k, q_codes, k_codes, s_q, s_k, tau)
+        o_sale, _ = attention_head(geo, q, k, v, mask)
+        errs.append(calibration_error(o_full, o_sale))
+        if errs[-1] < theta or n == max_halvings:
+            return tau, n, errs
+        tau = tau / 2.0
+    raise AssertionError("unreachable")

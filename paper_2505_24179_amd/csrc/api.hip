@@ -55,6 +55,8 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
       // max / sum per lane: 33 KB per 64-row block) and the order in which rows are issued
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
              (rows / kBlockQ) * (sizeof(int32_t) + 2048 * 16 + 256 * 4);
+    case SALE_WS_CALIBRATE:
+      return calibrate_workspace_bytes(p);
     default:
       return 0;
   }

@@ -112,7 +112,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
                                                                const bf16x8* __restrict__ vp,
                                                                const uint64_t* __restrict__ mask,
                                                                const int32_t* __restrict__ order,
-                                                               uint16_t* __restrict__ o, float* __restrict__ lse,
+                                                               uint16_t* __restrict__ o, float* __restrict__ o32,
+                                                               float* __restrict__ lse,
                                                                RowFilter flt, f32x4* __restrict__ st_o,
                                                                float* __restrict__ st_ml) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -392,10 +393,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        bf16x4 w;
+        if (o32) {     // calibration reads the output before it is rounded to bf16
+          f32x4 w;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][nt][4 * q4 + e] * inv);
-        *(bf16x4*)(orow + 32 * dt + 8 * q4) = w;
+          for (int e = 0; e < 4; ++e) w[e] = oacc[dt][nt][4 * q4 + e] * inv;
+          *(f32x4*)(o32 + row * kHeadDim + 4 * h + 32 * dt + 8 * q4) = w;
+        } else {
+          bf16x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][nt][4 * q4 + e] * inv);
+          *(bf16x4*)(orow + 32 * dt + 8 * q4) = w;
+        }
       }
     if (lse && h == 0) lse[row] = l_tot > 0.0f ? m_run[nt] * 0.08838834764831845f + __logf(l_tot) : -INFINITY;
   }
@@ -428,8 +436,9 @@ constexpr int kLongRow = 192;        // rows keeping more blocks than this are s
 constexpr int kWindowWords = 4;      // window width in 64-block mask words
 constexpr int kWindowMinWords = 8;   // sequences of up to 8 words (32K tokens) use one sweep per row
 
-static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
-                            const int32_t* row_counts, void* o, float* lse, void* ws, hipStream_t st) {
+// o: bf16 output, or (o32 != nullptr) fp32 output instead.
+int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
+                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st) {
   const Geo g = make_geo(p);
   const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
   u32x4* kp = (u32x4*)ws;
@@ -452,7 +461,7 @@ static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k
         if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
       }
       attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                    row_counts ? order : nullptr, (uint16_t*)o, lse, all, nullptr,
+                                                    row_counts ? order : nullptr, (uint16_t*)o, o32, lse, all, nullptr,
                                                     nullptr);
     } else {
       // Long rows (more than kLongRow kept blocks) carry most of the work and keep scattered blocks over the
@@ -468,16 +477,16 @@ static int launch_attn_rows(const sale_params_t* p, const void* q, const void* k
       for (int w = 0; w < g.words; w += kWindowWords) {
         const RowFilter lng = {row_counts, kLongRow + 1, 0x7FFFFFFF, w, kWindowWords};
         attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp,
-                                                      mask, order, (uint16_t*)o, lse, lng, st_o, st_ml);
+                                                      mask, order, (uint16_t*)o, o32, lse, lng, st_o, st_ml);
         if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
       }
       const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow, -1, 0};
       attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                    order, (uint16_t*)o, lse, shrt, nullptr, nullptr);
+                                                    order, (uint16_t*)o, o32, lse, shrt, nullptr, nullptr);
     }
   } else {
     attn_rows_kernel<4><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
-        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, lse, all, nullptr,
+        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, o32, lse, all, nullptr,
         nullptr);
   }
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
@@ -495,7 +504,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, nullptr, lse, ws, (hipStream_t)stream);
 }
 
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
@@ -505,5 +514,5 @@ extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, nullptr, lse, ws, (hipStream_t)stream);
 }

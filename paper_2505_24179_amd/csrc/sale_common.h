@@ -87,6 +87,10 @@ __device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
 }
 
 int validate_common(const sale_params_t* p, bool need_64x64);
+// attention launcher shared by the attention entry points and the calibration (attention.hip)
+int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
+                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st);
 Geo make_geo(const sale_params_t* p);
+size_t calibrate_workspace_bytes(const sale_params_t* p);
 
 }  // namespace sale

@@ -24,6 +24,7 @@ FLAG_STATS_CAUSAL = 1
 WS_SELECT = 1
 WS_SPARSE_ATTN = 2
 WS_DENSE_ATTN = 3
+WS_CALIBRATE = 4
 
 
 class _Params(ctypes.Structure):
@@ -72,6 +73,8 @@ _SIGS = {
     "sale_sparse_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "sale_calibrate_tau": (ctypes.c_int, [_pp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float, _i32, _vp, _vp, _vp,
+                                          _vp, _sz, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -176,3 +179,16 @@ def qk_int4_products(p: Params, q4, k4, q_head: int, q_block: int, k_block_begin
     _check(_lib.sale_qk_int4_products(ctypes.byref(p.c()), _ptr(q4), _ptr(k4), q_head, q_block,
                                       k_block_begin, k_block_end, _ptr(out), _stream()))
     return out
+
+
+def calibrate_tau(p: Params, q, k, v, tau0: float = 0.008, theta: float = 0.4, max_halvings: int = 8, ws=None):
+    """-> (tau f32 [Hq], err f32 [Hq], halvings i32 [Hq]); synchronises the current stream."""
+    dev = q.device
+    tau = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
+    err = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
+    halv = torch.empty(p.n_q_heads, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = torch.empty(max(1, workspace_bytes(p, WS_CALIBRATE)), dtype=torch.uint8, device=dev)
+    _check(_lib.sale_calibrate_tau(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), tau0, theta, max_halvings,
+                                   _ptr(tau), _ptr(err), _ptr(halv), _ptr(ws), ws.numel(), _stream()))
+    return tau, err, halv

@@ -24,7 +24,7 @@ def _declared_functions():
 
 def test_header_functions_are_exported(sale):
     names = _declared_functions()
-    assert {"sale_quantize_qk", "sale_select", "sale_sparse_attn", "sale_dense_attn",
+    assert {"sale_quantize_qk", "sale_select", "sale_sparse_attn", "sale_dense_attn", "sale_calibrate_tau",
             "sale_qk_int4_products", "sale_workspace_bytes", "sale_status_string"} <= set(names)
     lib = sale.raw()
     for n in names:
@@ -79,6 +79,19 @@ def test_argument_validation_launches_nothing(sale):
     assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, f, None, f, None, None, 0, None) == -4
     too_long = sale.Params(1, 1, 1, 64 * 64 * 64 + 64)
     assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, f, 1 << 40, None) == -3
+    # calibration
+    cal = lib.sale_calibrate_tau
+    cal.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_float, ctypes.c_float, ctypes.c_int32] + [ctypes.c_void_p] * 4 + \
+        [ctypes.c_size_t, ctypes.c_void_p]
+    gp = ctypes.byref(good.c())
+    aligned = ctypes.c_void_p(0x10000)
+    assert cal(gp, f, f, f, 0.008, 0.4, 6, None, None, None, aligned, 1 << 40, None) == -1
+    assert cal(gp, f, f, f, 0.0, 0.4, 6, f, None, None, aligned, 1 << 40, None) == -2       # tau0 outside (0, 1)
+    assert cal(gp, f, f, f, 0.008, -1.0, 6, f, None, None, aligned, 1 << 40, None) == -2
+    assert cal(gp, f, f, f, 0.008, 0.4, 65, f, None, None, aligned, 1 << 40, None) == -2
+    assert cal(gp, f, f, f, 0.008, 0.4, 6, f, None, None, aligned, 1024, None) == -4
+    assert cal(gp, f, f, f, 0.008, 0.4, 6, f, None, None, ctypes.c_void_p(0x10010), 1 << 40, None) == -4   # not 256-aligned
+    assert sale.workspace_bytes(good, sale.WS_CALIBRATE) > sale.workspace_bytes(good, sale.WS_SPARSE_ATTN)
     # parity hook range checks
     prod = lib.sale_qk_int4_products
     assert prod(ctypes.byref(good.c()), f, f, 4, 0, 0, 1, f, None) == -2

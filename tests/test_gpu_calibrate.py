@@ -1,0 +1,63 @@
+"""GPU parity of the per-head threshold calibration (Sec. 3.3) against the oracle: number of halvings,
+tau and Err at the returned tau, per head.  A head whose oracle Err lies within 2 % of theta at the
+step where the two could part is reported, not compared (its decision is inside the rounding noise)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sale_oracle as so
+from paper_2505_24179_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    (inputs.scaled(inputs.TOY, 1024, 1, 1, "calib-1k"), 0.012, 6),
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k"), 0.0064, 6),      # 3, 2, 2 and 0 halvings
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-cap"), 1e-6, 3),     # never satisfied: stops at the cap
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-loose"), 5.0, 6),    # satisfied at tau0
+]
+
+
+@pytest.mark.parametrize("w,theta,max_halvings", CASES, ids=[c[0].name for c in CASES])
+def test_calibration_matches_oracle(w, theta, max_halvings):
+    from paper_2505_24179_amd import sale
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    qd, kd, vd = (t.unsqueeze(0).cuda() for t in (q, k, v))
+    tau, err, halv = sale.calibrate_tau(p, qd, kd, vd, 0.008, theta, max_halvings)
+    tau, err, halv = tau.cpu().numpy(), err.cpu().numpy(), halv.cpu().numpy()
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    qf, kf, vf = q.float().numpy(), k.float().numpy(), v.float().numpy()
+    qc, qs = so.quantize_blocks(qf, 64)
+    kc, ks = so.quantize_blocks(kf, 64)
+    skipped = 0
+    for h in range(w.n_q_heads):
+        g = h // w.group
+        o_tau, o_n, o_errs = so.calibrate_head(geo, qf[h], kf[g], vf[g], qc[h], kc[g], qs[h], ks[g], 0.008, theta,
+                                               max_halvings)
+        print(f"[{w.name}] head {h}: gpu tau {tau[h]:.3e} halvings {halv[h]} err {err[h]:.5f} | "
+              f"oracle tau {o_tau:.3e} halvings {o_n} errs {[round(e, 5) for e in o_errs]}")
+        if any(abs(e - theta) <= 0.02 * theta for e in o_errs):
+            skipped += 1
+            continue
+        assert halv[h] == o_n
+        assert tau[h] == np.float32(o_tau)                 # tau0 / 2^n is exact in fp32
+        assert abs(err[h] - o_errs[-1]) <= 0.03 * o_errs[-1] + 1e-4
+    assert skipped <= 1
+
+
+def test_calibration_batch_entries_are_samples():
+    """Two samples: the thresholds must satisfy the bound on both, i.e. be the smaller of the two."""
+    from paper_2505_24179_amd import sale
+    w1 = inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "s1")
+    w2 = inputs.Workload(**{**w1.__dict__, "seed": w1.seed + 99, "name": "s2"})
+    (q1, k1, v1), (q2, k2, v2) = inputs.make_inputs(w1), inputs.make_inputs(w2)
+    p1, p2 = sale.Params(1, 4, 2, 2048), sale.Params(2, 4, 2, 2048)
+    theta = 0.0064
+    t1, _, _ = sale.calibrate_tau(p1, q1[None].cuda(), k1[None].cuda(), v1[None].cuda(), 0.008, theta, 6)
+    t2, _, _ = sale.calibrate_tau(p1, q2[None].cuda(), k2[None].cuda(), v2[None].cuda(), 0.008, theta, 6)
+    tb, _, _ = sale.calibrate_tau(p2, torch.stack([q1, q2]).cuda(), torch.stack([k1, k2]).cuda(),
+                                  torch.stack([v1, v2]).cuda(), 0.008, theta, 6)
+    print(t1.tolist(), t2.tolist(), tb.tolist())
+    assert torch.equal(tb, torch.minimum(t1, t2))
+    assert not torch.equal(t1, t2)
