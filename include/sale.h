@@ -52,6 +52,10 @@ typedef enum sale_status {
  * (flag clear) follows Alg. 1's comment: the statistics ignore the causal mask
  * inside the sink-local blocks. */
 #define SALE_FLAG_STATS_CAUSAL 1u
+/* sale_select estimates the attention weights of the middle blocks from the 16-bit Q, K instead of the
+ * 4-bit codes (the "w/o QK Quant" ablation of Appendix E); q4, k4 and the scales are then unused and may
+ * be NULL. */
+#define SALE_FLAG_SELECT_16BIT 2u
 
 typedef struct sale_params {
   int32_t batch;

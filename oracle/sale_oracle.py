@@ -150,9 +150,14 @@ def sink_local_stats(geo: Geometry, i: int, q_blk: np.ndarray, k: np.ndarray):
     return m, l
 
 
-def select_row(geo: Geometry, i: int, q_blk, k, q_codes_blk, k_codes, s_q_i: float, s_k, tau: float):
+def select_row(geo: Geometry, i: int, q_blk, k, q_codes_blk, k_codes, s_q_i: float, s_k, tau: float,
+               estimate: str = "int4"):
     """One query block of Alg. 1: returns (mask_row bool [N_k], margin float64
     [N_k], margin_thr float64 [N_k], thr float64 [b_q], m~, l~).
+
+    estimate = "int4": S~ from the 4-bit codes (the method).  estimate = "16bit": the
+    ablation of Appendix E ("w/o QK Quant"): S~ = S from the unquantized Q, K (the codes
+    and scales are then unused and may be None).
 
     mask_row[j] = 1 for j in I_SL; for a middle block j (0 <= j <= j_last, not
     in I_SL) it is 1 iff some row r has max_c S~[r, c] >= ln(tau * l~_r) + m~_r,
@@ -174,9 +179,17 @@ def select_row(geo: Geometry, i: int, q_blk, k, q_codes_blk, k_codes, s_q_i: flo
     middle = [j for j in range(jl + 1) if j not in isl]
     if middle:
         bk = geo.block_k
-        a = int_products(q_codes_blk, k_codes[: (jl + 1) * bk])      # [b_q, (jl+1) b_k]
+        if estimate == "int4":
+            a = int_products(q_codes_blk, k_codes[: (jl + 1) * bk])      # [b_q, (jl+1) b_k]
+        else:
+            assert estimate == "16bit"
+            s_full = (np.asarray(q_blk, dtype=np.float64) @ np.asarray(k[: (jl + 1) * bk], dtype=np.float64).T) \
+                / math.sqrt(geo.head_dim)
         for j in middle:
-            s_tilde = dequantize(a[:, j * bk:(j + 1) * bk], s_q_i, s_k[j], geo.head_dim)
+            if estimate == "int4":
+                s_tilde = dequantize(a[:, j * bk:(j + 1) * bk], s_q_i, s_k[j], geo.head_dim)
+            else:
+                s_tilde = s_full[:, j * bk:(j + 1) * bk]
             row_max = s_tilde.max(axis=1)
             r_star = int(np.argmax(row_max - thr))
             margin[j] = row_max[r_star] - thr[r_star]
@@ -185,7 +198,7 @@ def select_row(geo: Geometry, i: int, q_blk, k, q_codes_blk, k_codes, s_q_i: flo
     return mask, margin, margin_thr, thr, m, l
 
 
-def select_head(geo: Geometry, q, k, q_codes, k_codes, s_q, s_k, tau: float):
+def select_head(geo: Geometry, q, k, q_codes, k_codes, s_q, s_k, tau: float, estimate: str = "int4"):
     """Alg. 1 for one (query head, its KV head): M_bs bool [N_q, N_k] plus the
     margins and statistics of every query block."""
     bq = geo.block_q
@@ -198,7 +211,8 @@ def select_head(geo: Geometry, q, k, q_codes, k_codes, s_q, s_k, tau: float):
     for i in range(geo.n_q):
         rs = slice(i * bq, (i + 1) * bq)
         mask[i], margin[i], margin_thr[i], thr[rs], m[rs], l[rs] = select_row(
-            geo, i, q[rs], k, q_codes[rs], k_codes, float(s_q[i]), s_k, tau)
+            geo, i, q[rs], k, None if q_codes is None else q_codes[rs], k_codes,
+            0.0 if s_q is None else float(s_q[i]), s_k, tau, estimate)
     return mask, margin, margin_thr, thr, m, l
 
 

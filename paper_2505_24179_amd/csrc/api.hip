@@ -10,7 +10,7 @@ int validate_common(const sale_params_t* p, bool need_64x64) {
   if (p->n_q_heads % p->n_kv_heads != 0) return SALE_ERR_BAD_SHAPE;
   if (p->sink_blocks < 0 || p->local_blocks < 1) return SALE_ERR_BAD_SHAPE;
   if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
-  if (p->flags & ~SALE_FLAG_STATS_CAUSAL) return SALE_ERR_UNSUPPORTED;
+  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT)) return SALE_ERR_UNSUPPORTED;
   if (need_64x64) {
     if (p->block_q != kBlockQ || p->block_k != kBlockK) return SALE_ERR_UNSUPPORTED;
     if (p->seq_len > kMaxSeqLen) return SALE_ERR_UNSUPPORTED;

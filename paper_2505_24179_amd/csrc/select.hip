@@ -269,6 +269,68 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     if (lane == 0) row_counts[(size_t)(qh0 + a) * g.n_qb + i] = count[a];
 }
 
+// Appendix E ablation ("w/o QK Quant"): the same rule with the estimate taken from the 16-bit Q, K
+// themselves (S~ = S, bf16 MFMA with fp32 accumulation): four times the MFMA work of the FP6 estimate.
+__global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                       const float* __restrict__ thr, uint64_t* __restrict__ mask,
+                                                       int32_t* __restrict__ row_counts) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const Unit u = unit_of(g, blockIdx.x, wave);
+  if (!u.valid) return;
+  const int c = lane & 31, h = lane >> 5;
+  const float rsd = 0.08838834764831845f;   // 1 / sqrt(128)
+  bf16x8 qf[2][8];
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
+  }
+  float th[2];
+  th[0] = thr[(size_t)u.qh * g.seq + u.i * 64 + c];
+  th[1] = thr[(size_t)u.qh * g.seq + u.i * 64 + 32 + c];
+  uint64_t* mrow = mask + ((size_t)u.qh * g.n_qb + u.i) * g.words;
+  const int j_last = u.i;
+  int count = 0;
+  for (int wc = 0; wc < g.words; ++wc) {
+    uint64_t word = 0;
+    const int j_end = min(64, j_last + 1 - wc * 64);
+    for (int jj = 0; jj < j_end; ++jj) {
+      const int j = wc * 64 + jj;
+      if (in_sink_local(g, j, j_last)) { word |= 1ull << jj; continue; }
+      f32x16 acc[2][2];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const uint16_t* row = k + ((size_t)u.kvh * g.seq + j * 64 + 32 * mt + c) * kHeadDim + 8 * h;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          const bf16x8 a = *(const bf16x8*)(row + 16 * s);
+          acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][s], acc[mt][0], 0, 0, 0);
+          acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][s], acc[mt][1], 0, 0, 0);
+        }
+      }
+      bool pass = false;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        float mx = fmaxf(acc[0][nt][0], acc[1][nt][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, acc[0][nt][r]), acc[1][nt][r]);
+        pass = pass || (mx * rsd >= th[nt]);
+      }
+      word |= (uint64_t)(__ballot(pass) != 0ull) << jj;
+    }
+    if (lane == 0) mrow[wc] = word;
+    count += __popcll(word);
+  }
+  if (lane == 0) row_counts[(size_t)u.qh * g.n_qb + u.i] = count;
+}
+
 // Parity hook: the integer products themselves, one wave per key block, through the same
 // re-encoding and the same MFMA as the Selection-Pass.
 __global__ __launch_bounds__(64) void products_kernel(const uint8_t* __restrict__ q4_head, const uint8_t* __restrict__ k4_head,
@@ -312,7 +374,9 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
                            const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len,
                            uint64_t* block_mask, int32_t* row_counts, float* m_out, float* l_out, void* ws,
                            size_t ws_bytes, void* stream) {
-  if (!p || !q || !k || !q4 || !k4 || !q_scale || !k_scale || !tau || !block_mask || !row_counts) return SALE_ERR_NULL_ARG;
+  if (!p || !q || !k || !tau || !block_mask || !row_counts) return SALE_ERR_NULL_ARG;
+  const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
+  if (!est16 && (!q4 || !k4 || !q_scale || !k_scale)) return SALE_ERR_NULL_ARG;
   int rc = validate_common(p, true);
   if (rc != SALE_OK) return rc;
   if (tau_len != 1 && tau_len != p->n_q_heads) return SALE_ERR_BAD_SHAPE;
@@ -325,12 +389,17 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
   uint8_t* q6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
   uint8_t* k6 = q6 + (size_t)g.n_qh * g.n_qb * kX6BlockBytes;
   const long qblocks = (long)g.n_qh * g.n_qb, kblocks = (long)g.n_kvh * g.n_kb;
-  pack_fp6_kernel<<<dim3((unsigned)(qblocks + kblocks)), dim3(256), 0, st>>>(q4, q6, qblocks, k4, k6);
-  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  if (!est16) {
+    pack_fp6_kernel<<<dim3((unsigned)(qblocks + kblocks)), dim3(256), 0, st>>>(q4, q6, qblocks, k4, k6);
+    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  }
   stats_kernel<<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k, tau,
                                                                        tau_len, thr, m_out, l_out);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  if (g.group % 2 == 0) {
+  if (est16) {
+    select16_kernel<<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k, thr,
+                                                                            block_mask, row_counts);
+  } else if (g.group % 2 == 0) {
     const int t2 = (g.n_qb * (g.group / 2) + 3) / 4;
     select_kernel<2><<<dim3((unsigned)(t2 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr, block_mask,
                                                                           row_counts);

@@ -48,7 +48,11 @@ def test_full_size_sampled_parity(sale, name, n_units):
     ws = torch.empty(sale.workspace_bytes(p, sale.WS_SPARSE_ATTN), dtype=torch.uint8, device=dev)
     o_sparse, _ = sale.sparse_attn(p, qd, kd, vd, mask, counts, ws=ws)
     o_dense, lse_dense = sale.dense_attn(p, qd, kd, vd, want_lse=True, ws=ws)
+    p16 = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=sale.FLAG_SELECT_16BIT)
+    mask16, counts16, _, _ = sale.select(p16, qd, kd, None, None, None, None, tau)     # Appendix E ablation
     torch.cuda.synchronize()
+    print(f"[{name}] density with the 16-bit estimate "
+          f"{int(counts16.sum()) / (w.n_q_heads * p.n_q * (p.n_q + 1) // 2):.4f}", flush=True)
     print(f"[{name}] GPU path done, density "
           f"{int(counts.sum()) / (w.n_q_heads * p.n_q * (p.n_q + 1) // 2):.4f}", flush=True)
 
@@ -84,6 +88,9 @@ def test_full_size_sampled_parity(sale, name, n_units):
         a, b = compare_mask_row(got_row, row, margin, mthr)
         hard += a; soft += b
         assert int(counts[0, h, i]) == int(got_row.sum())
+        row16, margin16, mthr16, *_ = so.select_row(geo, i, qf, kf, None, None, 0.0, None, w.tau, "16bit")
+        a, b = compare_mask_row(words_to_bool(mask16[0, h, i].cpu().numpy(), p.n_k), row16, margin16, mthr16)
+        hard += a; soft += b
         # a6, a7: outputs of the sampled rows (the oracle attends over the GPU's mask row)
         ref_s, _ = so.attention_block(geo, i, qf, kf, vf, got_row)
         ref_d, ref_lse = so.attention_block(geo, i, qf, kf, vf, so.dense_mask(geo)[i] if w.seq_len <= 32768

@@ -288,3 +288,24 @@ def test_misaligned_or_small_workspace_is_rejected(sale):
     assert e.value.status == -4
     o, _ = sale.dense_attn(p, qd, kd, vd, ws=big[16:])       # aligned and large enough: fine
     assert torch.isfinite(o.float()).all()
+
+
+def test_select_16bit_estimate_matches_oracle(case, sale):
+    """Appendix E ablation: Selection-Pass with the estimate taken from the bf16 Q, K (no codes needed)."""
+    w, p0, q, k, v = case
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=sale.FLAG_SELECT_16BIT)
+    qd, kd = _dev(q, k)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    mask, counts, _, _ = sale.select(p, qd, kd, None, None, None, None, tau)
+    torch.cuda.synchronize()
+    got = words_to_bool(mask[0].cpu().numpy(), p.n_k)
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    qf, kf = f32(q), f32(k)
+    hard = soft = 0
+    for h in range(w.n_q_heads):
+        omask, margin, mthr, *_ = so.select_head(geo, qf[h], kf[h // w.group], None, None, None, None, w.tau, "16bit")
+        for i in range(geo.n_q):
+            a, b = compare_mask_row(got[h, i], omask[i], margin[i], mthr[i])
+            hard += a; soft += b
+        np.testing.assert_array_equal(counts[0, h].cpu().numpy(), got[h].sum(axis=1))
+    assert hard == 0 and soft <= 2

@@ -189,3 +189,38 @@ def test_sink_local_set_and_word_packing():
     row = np.zeros(130, dtype=bool); row[[0, 63, 64, 129]] = True
     w = so.pack_mask_words(row)
     assert w.dtype == np.uint64 and list(w) == [(1 << 63) | 1, 1, 2]
+
+
+@pytest.mark.parametrize("bq,bk,local,tau", [(64, 64, 2, 0.12), (64, 32, 4, 0.15)])
+def test_16bit_estimate_equals_library_logsumexp_rule_on_any_input(bq, bk, local, tau):
+    """Appendix E variant ("w/o QK Quant"): with S~ = S the rule is 'some element of the block has
+    S[r,c] - logsumexp_{c' in I_SL} S[r,c'] >= ln(tau)' for arbitrary inputs."""
+    q, k = _random_case(n=512, seed=8)
+    n, d = q.shape
+    geo = so.Geometry(n, d, bq, bk, sink_blocks=1, local_blocks=local)
+    mask, *_ = so.select_head(geo, q, k, None, None, None, None, tau, estimate="16bit")
+    s = (torch.from_numpy(q).double() @ torch.from_numpy(k).double().T) / math.sqrt(d)
+    expect = np.zeros((geo.n_q, geo.n_k), dtype=bool)
+    for i in range(geo.n_q):
+        j_last = ((i + 1) * bq - 1) // bk
+        isl = sorted(set([0]) | set(range(max(0, j_last - local + 1), j_last + 1)))
+        cols = torch.cat([torch.arange(j * bk, (j + 1) * bk) for j in isl])
+        rows = slice(i * bq, (i + 1) * bq)
+        lse = torch.logsumexp(s[rows][:, cols], dim=1)
+        for j in range(j_last + 1):
+            rel = s[rows, j * bk:(j + 1) * bk] - lse[:, None] - math.log(tau)
+            expect[i, j] = j in isl or bool((rel >= 0).any())
+            assert j in isl or rel.abs().min() > 1e-9
+    np.testing.assert_array_equal(mask, expect)
+    dm = so.dense_mask(geo)
+    assert 0.2 < mask.sum() / dm.sum() < 0.95
+
+
+def test_16bit_and_int4_estimates_coincide_on_the_lossless_grid():
+    q, k = _grid_inputs(256, 16, 8, 21)
+    geo = so.Geometry(256, 16, 16, 8, 1, 4)
+    qc, sq = so.quantize_blocks(q[None], 16)
+    kc, sk = so.quantize_blocks(k[None], 8)
+    m4, *_ = so.select_head(geo, q, k, qc[0], kc[0], sq[0], sk[0], 0.2)
+    m16, *_ = so.select_head(geo, q, k, None, None, None, None, 0.2, estimate="16bit")
+    np.testing.assert_array_equal(m4, m16)
