@@ -20,10 +20,11 @@
  *   Query head h reads KV head h / (n_q_heads / n_kv_heads)  (GQA).
  * - Return value: SALE_OK (0) or a negative sale_status.  Arguments are checked
  *   before anything is launched; a failed check launches nothing.
- * - Supported geometry: head_dim = 128; block_q = block_k = 64; seq_len a
- *   multiple of 64; n_q_heads a multiple of n_kv_heads.  (sale_quantize_qk
- *   alone also accepts block sizes of 32.)  Anything else returns
- *   SALE_ERR_UNSUPPORTED.
+ * - Supported geometry: head_dim = 128; block_q = 64; block_k = 64, or 32
+ *   (the paper's shape, Sec. 4.1) for sale_quantize_qk, sale_select and
+ *   sale_qk_int4_products; seq_len a multiple of 64 and at most 4096 key
+ *   blocks; n_q_heads a multiple of n_kv_heads.  (sale_quantize_qk alone also
+ *   accepts block_q = 32.)  Anything else returns SALE_ERR_UNSUPPORTED.
  *
  * Notation follows the paper: N = seq_len, d = head_dim, b_q / b_k block sizes,
  * N_q = N / b_q, N_k = N / b_k, M_bs the block-level sparse mask (Sec. 3.1),
@@ -56,6 +57,12 @@ typedef enum sale_status {
  * 4-bit codes (the "w/o QK Quant" ablation of Appendix E); q4, k4 and the scales are then unused and may
  * be NULL. */
 #define SALE_FLAG_SELECT_16BIT 2u
+/* Segment rule for the local area (Appendix C): the middle key blocks of a row (those after the sink
+ * blocks) are taken in segments of 4; the fewer-than-4 blocks left over before the local_blocks
+ * diagonal-side blocks join the local area, i.e. with j_last the last causally visible key block
+ *   local(i) = local_blocks + max(0, j_last + 1 - sink_blocks - local_blocks) mod 4.
+ * They are always kept and feed the statistics like the other local blocks. */
+#define SALE_FLAG_SEGMENT_LOCAL 4u
 
 typedef struct sale_params {
   int32_t batch;

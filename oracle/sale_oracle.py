@@ -112,6 +112,7 @@ class Geometry:
     sink_blocks: int = 1
     local_blocks: int = 4
     stats_causal: bool = False   # False: the statistics ignore the causal mask (Alg. 1 comment)
+    segment: int = 0             # > 0: segment rule of Appendix C with that many key blocks per segment
 
     @property
     def n_q(self) -> int:
@@ -125,12 +126,22 @@ class Geometry:
         """Last key block any row of query block i may attend causally."""
         return ((i + 1) * self.block_q - 1) // self.block_k
 
+    def local_count(self, i: int) -> int:
+        """Key blocks in the local area of query block i.  Without segments: local_blocks.
+        With segments (Appendix C) the middle blocks, i.e. those between the sink blocks and
+        the local_blocks blocks at the diagonal, are taken `segment` at a time from the left
+        and the ones left over at the end of the row count as local too."""
+        if self.segment <= 0:
+            return self.local_blocks
+        middle = self.j_last(i) + 1 - self.sink_blocks - self.local_blocks
+        return self.local_blocks + (middle % self.segment if middle > 0 else 0)
+
     def sink_local(self, i: int) -> list:
         """I_SL of Alg. 1 in key-block units: the sink blocks and the
-        local_blocks blocks ending at (and including) the diagonal one."""
+        local_count(i) blocks ending at (and including) the diagonal one."""
         jl = self.j_last(i)
         s = set(range(min(self.sink_blocks, jl + 1)))
-        s |= set(range(max(0, jl - self.local_blocks + 1), jl + 1))
+        s |= set(range(max(0, jl - self.local_count(i) + 1), jl + 1))
         return sorted(s)
 
 

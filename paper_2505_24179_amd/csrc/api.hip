@@ -3,19 +3,19 @@
 
 namespace sale {
 
-int validate_common(const sale_params_t* p, bool need_64x64) {
+int validate_common(const sale_params_t* p, GeomClass cls) {
   if (p->batch <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->seq_len <= 0) return SALE_ERR_BAD_SHAPE;
   if (p->block_q <= 0 || p->block_k <= 0) return SALE_ERR_BAD_SHAPE;
   if (p->seq_len % p->block_q != 0 || p->seq_len % p->block_k != 0) return SALE_ERR_BAD_SHAPE;
   if (p->n_q_heads % p->n_kv_heads != 0) return SALE_ERR_BAD_SHAPE;
   if (p->sink_blocks < 0 || p->local_blocks < 1) return SALE_ERR_BAD_SHAPE;
   if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
-  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT)) return SALE_ERR_UNSUPPORTED;
-  if (need_64x64) {
-    if (p->block_q != kBlockQ || p->block_k != kBlockK) return SALE_ERR_UNSUPPORTED;
-    if (p->seq_len > kMaxSeqLen) return SALE_ERR_UNSUPPORTED;
-  } else {
-    if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
+  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL)) return SALE_ERR_UNSUPPORTED;
+  if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
+  if (cls != kGeomQuantize) {
+    if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
+    if (cls == kGeomAttention && p->block_k != kBlockK) return SALE_ERR_UNSUPPORTED;
+    if (p->seq_len / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
   }
   // 32-bit index guards used by the kernels
   if ((long)p->batch * p->n_q_heads * (long)(p->seq_len / 32) > 0x7FFFFFFFL) return SALE_ERR_UNSUPPORTED;
@@ -30,10 +30,12 @@ Geo make_geo(const sale_params_t* p) {
   g.group = p->n_q_heads / p->n_kv_heads;
   g.seq = p->seq_len;
   g.n_qb = p->seq_len / kBlockQ;
-  g.n_kb = p->seq_len / kBlockK;
+  g.bk = p->block_k;
+  g.n_kb = p->seq_len / p->block_k;
   g.words = (g.n_kb + 63) / 64;
   g.sink_blocks = p->sink_blocks;
   g.local_blocks = p->local_blocks;
+  g.seg = (p->flags & SALE_FLAG_SEGMENT_LOCAL) ? kSegmentBlocks : 0;
   g.stats_causal = (p->flags & SALE_FLAG_STATS_CAUSAL) ? 1 : 0;
   return g;
 }
@@ -43,7 +45,7 @@ Geo make_geo(const sale_params_t* p) {
 using namespace sale;
 
 extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
-  if (!p || validate_common(p, true) != SALE_OK) return 0;
+  if (!p || validate_common(p, which_call == SALE_WS_SELECT ? kGeomSelect : kGeomAttention) != SALE_OK) return 0;
   const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
   switch (which_call) {
     case SALE_WS_SELECT:

@@ -500,7 +500,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
                                 const uint64_t* block_mask, const int32_t* row_counts, void* o, float* lse, void* ws,
                                 size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !block_mask || !o) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, true);
+  int rc = validate_common(p, kGeomAttention);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
@@ -510,7 +510,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
                                void* ws, size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !o) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, true);
+  int rc = validate_common(p, kGeomAttention);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;

@@ -79,7 +79,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
                                   float theta, int32_t max_halvings, float* tau_out, float* err_out,
                                   int32_t* halvings_out, void* ws, size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !tau_out) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, true);
+  int rc = validate_common(p, kGeomAttention);
   if (rc != SALE_OK) return rc;
   if (!(tau0 > 0.0f && tau0 < 1.0f) || !(theta > 0.0f) || max_halvings < 0 || max_halvings > 64) return SALE_ERR_BAD_SHAPE;
   if (p->n_q_heads > 4096 || p->batch > 4096) return SALE_ERR_UNSUPPORTED;

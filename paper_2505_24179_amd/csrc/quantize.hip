@@ -79,7 +79,7 @@ using namespace sale;
 extern "C" int sale_quantize_qk(const sale_params_t* p, const void* q, const void* k, uint8_t* q4, uint8_t* k4,
                                 float* q_scale, float* k_scale, void* stream) {
   if (!p || !q || !k || !q4 || !k4 || !q_scale || !k_scale) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, false);
+  int rc = validate_common(p, kGeomQuantize);
   if (rc != SALE_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   const long rows_q = (long)p->batch * p->n_q_heads * p->seq_len;

@@ -23,9 +23,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int kHeadDim = 128;   // d
 constexpr int kBlockQ = 64;     // b_q
-constexpr int kBlockK = 64;     // b_k
+constexpr int kBlockK = 64;     // b_k of the Computation-Pass (the Selection-Pass also takes 32)
+constexpr int kSegmentBlocks = 4;            // key blocks per segment (Appendix C)
 constexpr int kMaskWordsMax = 64;            // longest mask row, in 64-bit words
-constexpr int kMaxSeqLen = kMaskWordsMax * 64 * kBlockK;   // 262144 tokens
+constexpr int kMaxSeqLen = kMaskWordsMax * 64 * kBlockK;   // 262144 tokens (131072 with b_k = 32)
 
 // Flattened geometry handed to kernels.
 struct Geo {
@@ -35,10 +36,12 @@ struct Geo {
   int group;       // n_q_heads / n_kv_heads
   int seq;         // N
   int n_qb;        // N / 64
-  int n_kb;        // N / 64
+  int bk;          // b_k: 64 or 32
+  int n_kb;        // N / b_k
   int words;       // ceil(n_kb / 64)
   int sink_blocks;
   int local_blocks;
+  int seg;         // segment size in key blocks (0 = no segment rule for the local area)
   int stats_causal;
 };
 
@@ -86,7 +89,10 @@ __device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
   return u;
 }
 
-int validate_common(const sale_params_t* p, bool need_64x64);
+// Which geometry a call accepts: any mix of 32 / 64 (quantization), b_q = 64 with b_k = 64 or 32
+// (Selection-Pass), 64 x 64 only (Computation-Pass, calibration).
+enum GeomClass { kGeomQuantize, kGeomSelect, kGeomAttention };
+int validate_common(const sale_params_t* p, GeomClass cls);
 // attention launcher shared by the attention entry points and the calibration (attention.hip)
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
                      const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st);

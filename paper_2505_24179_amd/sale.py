@@ -22,6 +22,7 @@ _lib = ctypes.CDLL(_LIB_PATH)
 OK = 0
 FLAG_STATS_CAUSAL = 1
 FLAG_SELECT_16BIT = 2
+FLAG_SEGMENT_LOCAL = 4
 WS_SELECT = 1
 WS_SPARSE_ATTN = 2
 WS_DENSE_ATTN = 3

@@ -64,10 +64,12 @@ def test_argument_validation_launches_nothing(sale):
     assert _call_quant(sale, sale.Params(1, 4, 2, 256, head_dim=64)) == -3
     assert _call_quant(sale, sale.Params(1, 4, 2, 256, block_q=16, block_k=16)) == -3
     assert _call_quant(sale, sale.Params(1, 4, 2, 256, flags=8)) == -3
-    # select: paper-shape 64x32 blocks are not built yet; workspace too small; bad tau_len
+    # select: query blocks must be 64 rows, at most 4096 key blocks; workspace too small; bad tau_len
     sel = lib.sale_select
-    p6432 = sale.Params(1, 4, 2, 256, block_k=32, local_blocks=8)
-    assert sel(ctypes.byref(p6432.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 1 << 30, None) == -3
+    p3232 = sale.Params(1, 4, 2, 256, block_q=32, block_k=32)
+    assert sel(ctypes.byref(p3232.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 1 << 30, None) == -3
+    plong = sale.Params(1, 1, 1, 32 * 4096 + 64, block_k=32)
+    assert sel(ctypes.byref(plong.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 1 << 40, None) == -3
     assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 1, f, f, None, None, f, 16, None) == -4
     assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None, 0, None) == -4
     assert sel(ctypes.byref(good.c()), f, f, f, f, f, f, f, 3, f, f, None, None, f, 1 << 30, None) == -2
@@ -77,6 +79,9 @@ def test_argument_validation_launches_nothing(sale):
     assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, f, f, None, f, 16, None) == -4
     assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, None, None, f, None, f, 1 << 30, None) == -1
     assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, f, None, f, None, None, 0, None) == -4
+    p6432 = sale.Params(1, 4, 2, 256, block_k=32)      # the Computation-Pass takes 64 x 64 blocks only
+    assert lib.sale_dense_attn(ctypes.byref(p6432.c()), f, f, f, f, None, f, 1 << 30, None) == -3
+    assert lib.sale_sparse_attn(ctypes.byref(p6432.c()), f, f, f, f, None, f, None, f, 1 << 30, None) == -3
     too_long = sale.Params(1, 1, 1, 64 * 64 * 64 + 64)
     assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, f, 1 << 40, None) == -3
     # calibration

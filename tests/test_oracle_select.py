@@ -224,3 +224,70 @@ def test_16bit_and_int4_estimates_coincide_on_the_lossless_grid():
     m4, *_ = so.select_head(geo, q, k, qc[0], kc[0], sq[0], sk[0], 0.2)
     m16, *_ = so.select_head(geo, q, k, None, None, None, None, 0.2, estimate="16bit")
     np.testing.assert_array_equal(m4, m16)
+
+
+def _segment_walk(j_last, sink, base_local, seg):
+    """Appendix C's local area, by walking the row instead of a formula: after the sink blocks, whole
+    segments are peeled off from the left for as long as `seg` middle blocks remain before the
+    base_local blocks at the diagonal; whatever is left is the local area."""
+    blocks = list(range(j_last + 1))
+    pos = min(sink, len(blocks))
+    while len(blocks) - pos - base_local >= seg:
+        pos += seg
+    return sorted(set(blocks[:sink]) | set(blocks[max(pos, 0):] if len(blocks) - sink > base_local else blocks))
+
+
+def test_segment_rule_local_area_matches_walk_and_paper_bounds():
+    """Paper shape (Sec. 4.1, Appendix C): b_q = 64, b_k = 32, sink 1 block, local at least 128 tokens =
+    4 blocks, segments of 4 blocks: the local area holds at least 128 and fewer than 256 tokens and
+    the middle blocks split into whole segments."""
+    geo = so.Geometry(64 * 40, 128, 64, 32, sink_blocks=1, local_blocks=4, segment=4)
+    plain = so.Geometry(64 * 40, 128, 64, 32, sink_blocks=1, local_blocks=4)
+    seen = set()
+    for i in range(geo.n_q):
+        jl = geo.j_last(i)
+        isl = geo.sink_local(i)
+        assert isl == _segment_walk(jl, 1, 4, 4)
+        assert set(plain.sink_local(i)) <= set(isl)
+        middle = [j for j in range(jl + 1) if j not in isl]
+        assert len(middle) % 4 == 0
+        if middle:
+            assert middle == list(range(1, 1 + len(middle)))            # contiguous, right after the sink
+            local_tokens = (jl + 1 - middle[-1] - 1) * 32
+            assert 128 <= local_tokens < 256
+            assert geo.local_count(i) * 32 == local_tokens
+            seen.add(geo.local_count(i))
+        else:
+            assert isl == list(range(jl + 1))
+    assert len(seen) >= 2                                               # the remainder really varies
+    # other segment sizes and bases, against the same walk
+    for sink, base, seg, bk in [(2, 3, 4, 32), (1, 4, 2, 64), (0, 1, 3, 32)]:
+        g2 = so.Geometry(64 * 24, 128, 64, bk, sink_blocks=sink, local_blocks=base, segment=seg)
+        for i in range(g2.n_q):
+            assert g2.sink_local(i) == _segment_walk(g2.j_last(i), sink, base, seg), (sink, base, seg, i)
+
+
+def test_segment_rule_mask_is_the_plain_mask_with_the_remainder_kept():
+    """On the lossless grid the segment variant equals the library logsumexp rule taken over the
+    enlarged sink-local set; and every block it adds to I_SL is kept."""
+    n, d, bq, bk = 512, 16, 16, 8
+    q, k = _grid_inputs(n, d, bk, 21)
+    geo = so.Geometry(n, d, bq, bk, sink_blocks=1, local_blocks=2, segment=4)
+    qc, sq = so.quantize_blocks(q[None], bq)
+    kc, sk = so.quantize_blocks(k[None], bk)
+    tau = 0.2
+    mask, *_ = so.select_head(geo, q, k, qc[0], kc[0], sq[0], sk[0], tau)
+    s = (torch.from_numpy(q).double() @ torch.from_numpy(k).double().T) / math.sqrt(d)
+    expect = np.zeros_like(mask)
+    for i in range(geo.n_q):
+        jl = ((i + 1) * bq - 1) // bk
+        isl = _segment_walk(jl, 1, 2, 4)
+        cols = torch.cat([torch.arange(j * bk, (j + 1) * bk) for j in isl])
+        rows = slice(i * bq, (i + 1) * bq)
+        lse = torch.logsumexp(s[rows][:, cols], dim=1)
+        for j in range(jl + 1):
+            rel = s[rows, j * bk:(j + 1) * bk] - lse[:, None] - math.log(tau)
+            assert j in isl or rel.abs().min() > 1e-9
+            expect[i, j] = j in isl or bool((rel >= 0).any())
+    np.testing.assert_array_equal(mask, expect)
+    assert 0.1 < mask.sum() / so.dense_mask(geo).sum() < 0.95
