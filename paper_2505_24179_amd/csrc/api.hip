@@ -14,7 +14,6 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
   if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
   if (cls != kGeomQuantize) {
     if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
-    if (cls == kGeomAttention && p->block_k != kBlockK) return SALE_ERR_UNSUPPORTED;
     if (p->seq_len / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
   }
   // 32-bit index guards used by the kernels
@@ -45,7 +44,7 @@ Geo make_geo(const sale_params_t* p) {
 using namespace sale;
 
 extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
-  if (!p || validate_common(p, which_call == SALE_WS_SELECT ? kGeomSelect : kGeomAttention) != SALE_OK) return 0;
+  if (!p || validate_common(p, kGeomPath) != SALE_OK) return 0;
   const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
   switch (which_call) {
     case SALE_WS_SELECT:

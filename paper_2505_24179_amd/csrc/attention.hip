@@ -106,7 +106,10 @@ struct RowFilter {
 };
 
 // order: optional [kv head][rank] -> unit id within the KV head (block * group + head-in-group).
-template <int WAVES>
+// BK32: the mask has one bit per 32 keys (b_k = 32) instead of one per 64.  The kernel always works on
+// pairs of 32-key half-tiles; with b_k = 64 a pair is the two halves of one block, with b_k = 32 it is any
+// two kept half-tiles of the row (the operand copies K', V' are addressable by half-tile).
+template <int WAVES, bool BK32>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
                                                                const bf16x8* __restrict__ kp,
                                                                const bf16x8* __restrict__ vp,
@@ -137,14 +140,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 
   // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
   const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
-  const int last_word = u.i >> 6;
+  const int j_last = BK32 ? 2 * u.i + 1 : u.i;      // last causally visible mask bit of the row
+  const int last_word = j_last >> 6;
   if (flt.win_word > last_word) return;
   const int word_lo = flt.win_word >= 0 ? flt.win_word : 0;
   const int word_hi = flt.win_word >= 0 ? min(flt.win_word + flt.win_words - 1, last_word) : last_word;
   const bool resume = flt.win_word > 0, park = flt.win_word >= 0 && word_hi < last_word;
   auto row_word = [&](int wc) -> uint64_t {
     const int lo = wc * 64;
-    const uint64_t causal = u.i >= lo + 63 ? ~0ull : ((2ull << (u.i - lo)) - 1ull);
+    const uint64_t causal = j_last >= lo + 63 ? ~0ull : ((2ull << (j_last - lo)) - 1ull);
     return mrow ? (mrow[wc] & causal) : causal;
   };
 
@@ -157,18 +161,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
   }
-  const bf16x8* kt = kp + (size_t)u.kvh * g.n_kb * 1024 + lane;
-  const bf16x8* vt = vp + (size_t)u.kvh * g.n_kb * 1024 + lane;
-  // A block is processed as two half-tiles of 32 keys (mt = 0, 1).  K operands of half-tile mt:
-  // kf[mt][s]; V operands of half-tile mt: vf[mt][dt][s2] (k-steps s = 2*mt + s2 of the tile).
+  const bf16x8* kt = kp + (size_t)u.kvh * g.seq * 16 + lane;     // 1024 16-byte chunks per 64 keys
+  const bf16x8* vt = vp + (size_t)u.kvh * g.seq * 16 + lane;
+  // Work proceeds in pairs of 32-key half-tiles held in slots 0 and 1; half-tile hb covers keys
+  // 32hb .. 32hb+31 (half hb % 2 of the 64-key tile hb / 2 of K', V').  K operands of slot mt: kf[mt][s];
+  // V operands of slot mt: vf[mt][dt][s2].
   bf16x8 kf[2][8], vf[2][4][2];
-  auto load_k = [&](int j, int mt) __attribute__((always_inline)) {
-    const bf16x8* t = kt + (size_t)j * 1024 + mt * 512;
+  auto load_k = [&](int hb, int mt) __attribute__((always_inline)) {
+    const bf16x8* t = kt + (size_t)hb * 512;
 #pragma unroll
     for (int s = 0; s < 8; ++s) kf[mt][s] = t[s * 64];
   };
-  auto load_v = [&](int j, int mt) __attribute__((always_inline)) {
-    const bf16x8* t = vt + (size_t)j * 1024 + mt * 128;
+  auto load_v = [&](int hb, int mt) __attribute__((always_inline)) {
+    const bf16x8* t = vt + (size_t)(hb >> 1) * 1024 + (hb & 1) * 128;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -243,15 +248,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
         oacc[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[mt][dt][s2], P[mt][1][s2], oacc[dt][1], 0, 0, 0);
       }
   };
-  // Row maxima of half-tile mt (after causal masking on the diagonal block): mx[nt].
+  // Row maxima of the half-tile in slot mt (after causal masking where `diag` asks for it): mx[nt].
+  // koff[mt]: first key of the slot's half-tile minus the first query row of the block (b_k = 32 only;
+  // with b_k = 64 the masked pair is the diagonal block: 0 and 32).  A huge koff empties the slot.
   float mx[2];
+  int koff[2] = {0, 32};
   auto max_half = [&](int mt, auto diag) __attribute__((always_inline)) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
       if constexpr (decltype(diag)::value) {
+        const int ko = BK32 ? koff[mt] : 32 * mt;
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
+          if (ko + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
       }
       float v = fmaxf(S[mt][nt][0], S[mt][nt][1]);
 #pragma unroll
@@ -266,7 +275,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) {
         const float m_new = fmaxf(m_run[nt], mx[nt]);
-        const float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
+        float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
+        // b_k = 32: a query row may have seen no key yet (its first half-tile lies above the diagonal)
+        if constexpr (BK32) alpha = m_new == -INFINITY ? 1.0f : alpha;
         l_run[nt] *= alpha;
         m_run[nt] = m_new;
 #pragma unroll
@@ -288,7 +299,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      const float mb = m_run[nt] * cs;
+      const float mb = (BK32 && m_run[nt] == -INFINITY) ? 0.0f : m_run[nt] * cs;
       float sum = l_run[nt];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
@@ -308,16 +319,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     }
   };
 
-  // One kept block j.  first: no previous block whose half 1 is still to be multiplied.  last: no
-  // next block (j_next is then unused).  diag: j is the diagonal block (always the last of a row).
+  // One pair of half-tiles (slot 0: cur.a, slot 1: cur.b).  first: no previous pair whose slot 1 is still
+  // to be multiplied.  last: no next pair (nxt is then unused).  diag: apply the causal mask (and, with
+  // b_k = 32, the emptying of a slot that has no half-tile).
   // Every load and MFMA of a variant is unconditional, so the compiler can count outstanding loads
   // exactly and never has to drain the queue.
-  auto block_step = [&](int j, int j_next, auto first, auto last, auto diag) __attribute__((always_inline)) {
+  struct Pair { int a, b; };
+  auto block_step = [&](Pair cur, Pair nxt, auto first, auto last, auto diag) __attribute__((always_inline)) {
     constexpr bool kLast = decltype(last)::value;
     // stage A
     if constexpr (!decltype(first)::value) pv_half(1);
     max_half(0, diag);
-    load_v(j, 1);
+    load_v(cur.b, 1);
     if constexpr (!decltype(first)::value) { SALE_PIPE(16, 2, 1) }
     rescale();
     // stage B
@@ -326,11 +339,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     // stage C
     pv_half(0);
     max_half(1, diag);
-    if constexpr (!kLast) { load_k(j_next, 1); load_v(j_next, 0); }
+    if constexpr (!kLast) { load_k(nxt.b, 1); load_v(nxt.a, 0); }
     SALE_PIPE(16, 6, 0)
     SALE_PIPE(16, 2, 1)
     rescale();
-    // stage D (kf[0] of the next block was requested before stage A)
+    // stage D (kf[0] of the next pair was requested before stage A)
     if constexpr (!kLast) qk_half(0);
     exp_half(1);
     if constexpr (!kLast) { SALE_PIPE(16, 6, 0) }
@@ -338,30 +351,69 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   const auto T = std::true_type{};
   const auto F = std::false_type{};
 
-  int j_cur = next_block();
-  if (j_cur >= 0) {
-    load_k(j_cur, 0);
-    load_k(j_cur, 1);
-    load_v(j_cur, 0);
-    qk_half(0);
-    int j_next = next_block();
-    if (j_next < 0) {
-      if (j_cur == u.i) block_step(j_cur, 0, T, T, T); else block_step(j_cur, 0, T, T, F);
+  // b_k = 32: an odd number of kept half-tiles leaves one without a partner.  It goes FIRST, next to an
+  // emptied slot 1 (which re-reads the same half-tile), so that every later pair is complete and the
+  // half-tiles of the diagonal block, the largest indices of a row, fall into the last pair.  The first
+  // and the last pair of a sweep take the masked variant.
+  bool lone_first = false;
+  if constexpr (BK32) {
+    const int wcl = word_lo + lane;
+    const int bits = wcl <= word_hi ? __popcll(row_word(wcl)) : 0;
+    lone_first = (__popcll(__builtin_amdgcn_ballot_w64((bits & 1) != 0)) & 1) != 0;
+  }
+  constexpr int kEmptySlot = 1 << 24;
+  auto next_pair = [&](Pair& pr) -> bool {
+    const int a = next_block();
+    if (a < 0) return false;
+    if constexpr (BK32) {
+      pr.a = a;
+      const int b = next_block();
+      pr.b = b < 0 ? a : b;      // (b < 0 cannot happen once the lone half-tile has gone first)
     } else {
-      // the list is read one block ahead of the loads so that no control flow separates the stages
-      load_k(j_next, 0);
-      int j_after = next_block();
-      block_step(j_cur, j_next, T, F, F);
-      j_cur = j_next;
-      j_next = j_after;
-      while (j_next >= 0) {
-        load_k(j_next, 0);
-        j_after = next_block();
-        block_step(j_cur, j_next, F, F, F);
-        j_cur = j_next;
-        j_next = j_after;
+      pr.a = 2 * a;
+      pr.b = 2 * a + 1;
+    }
+    return true;
+  };
+  auto set_koff = [&](Pair pr, bool empty_b) {
+    if constexpr (BK32) {
+      koff[0] = (pr.a - 2 * u.i) * 32;
+      koff[1] = empty_b ? kEmptySlot : (pr.b - 2 * u.i) * 32;
+    }
+  };
+
+  Pair pc = {0, 0}, pn = {0, 0}, pa = {0, 0};
+  bool have;
+  if (BK32 && lone_first) {
+    const int a = next_block();
+    have = a >= 0;
+    pc.a = pc.b = a;
+  } else {
+    have = next_pair(pc);
+  }
+  if (have) {
+    load_k(pc.a, 0);
+    load_k(pc.b, 1);
+    load_v(pc.a, 0);
+    qk_half(0);
+    bool has_next = next_pair(pn);
+    set_koff(pc, lone_first);
+    if (!has_next) {
+      if (BK32 || pc.a == 2 * u.i) block_step(pc, pc, T, T, T); else block_step(pc, pc, T, T, F);
+    } else {
+      // the list is read one pair ahead of the loads so that no control flow separates the stages
+      load_k(pn.a, 0);
+      bool has_aft = next_pair(pa);
+      if constexpr (BK32) block_step(pc, pn, T, F, T); else block_step(pc, pn, T, F, F);
+      pc = pn; pn = pa; has_next = has_aft;
+      while (has_next) {
+        load_k(pn.a, 0);
+        has_aft = next_pair(pa);
+        block_step(pc, pn, F, F, F);
+        pc = pn; pn = pa; has_next = has_aft;
       }
-      if (j_cur == u.i) block_step(j_cur, 0, F, T, T); else block_step(j_cur, 0, F, T, F);
+      set_koff(pc, false);
+      if (BK32 || pc.a == 2 * u.i) block_step(pc, pc, F, T, T); else block_step(pc, pc, F, T, F);
     }
     pv_half(1);
   }
@@ -432,11 +484,51 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
     order[(size_t)kvh * units + atomicAdd(&bin[count_of(id)], 1)] = id;
 }
 
-constexpr int kLongRow = 192;        // rows keeping more blocks than this are swept window by window
-constexpr int kWindowWords = 4;      // window width in 64-block mask words
-constexpr int kWindowMinWords = 8;   // sequences of up to 8 words (32K tokens) use one sweep per row
+// All three in units of 64 keys (scaled by 64 / b_k for a mask with one bit per b_k keys).
+constexpr int kLongRow = 192;        // rows keeping more than this (12K tokens) are swept window by window
+constexpr int kWindowWords = 4;      // window width in mask words of 64 x 64 keys
+constexpr int kWindowMinWords = 8;   // sequences of up to 32K tokens use one sweep per row
 
-// o: bf16 output, or (o32 != nullptr) fp32 output instead.
+namespace {
+
+template <bool BK32>
+int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, const uint64_t* mask,
+                       const int32_t* row_counts, int32_t* order, uint16_t* o, float* o32, float* lse, f32x4* st_o,
+                       float* st_ml, hipStream_t st) {
+  const int units = g.n_qb * g.group;
+  const int f = BK32 ? 2 : 1;          // mask bits per 64 keys
+  const dim3 grid((unsigned)(units * g.n_kvh));
+  const RowFilter all = {nullptr, 0, 0, -1, 0};
+  if (row_counts) {
+    order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
+    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  }
+  if (!row_counts || g.words <= kWindowMinWords * f) {
+    attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, row_counts ? order : nullptr, o, o32, lse, all,
+                                                        nullptr, nullptr);
+    return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
+  }
+  // Long rows carry most of the work and keep scattered blocks over the whole sequence: swept
+  // independently they miss L2 on most loads.  They are processed one window of 16K tokens (8 MB of K', V'
+  // per KV head) at a time, all rows together, so that the window is served by the L2 of the XCD that owns
+  // the KV head and by the memory-side cache; their accumulators wait in the workspace in between.
+  // Measured at 128K tokens: 218 GB of L2 fills and 50.7 ms in one sweep per row, 50 GB and 37.3 ms with
+  // windows; up to 32K tokens one sweep is faster.
+  // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
+  for (int w = 0; w < g.words; w += kWindowWords * f) {
+    const RowFilter lng = {row_counts, kLongRow * f + 1, 0x7FFFFFFF, w, kWindowWords * f};
+    attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, order, o, o32, lse, lng, st_o, st_ml);
+    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  }
+  const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow * f, -1, 0};
+  attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, order, o, o32, lse, shrt, nullptr, nullptr);
+  return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
+}
+
+}  // namespace
+
+// o: bf16 output, or (o32 != nullptr) fp32 output instead.  mask == nullptr: dense causal attention
+// (independent of b_k).
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
                      const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st) {
   const Geo g = make_geo(p);
@@ -448,47 +540,20 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
   float* st_ml = (float*)(st_o + n_units * 2048);
   int32_t* order = (int32_t*)(st_ml + n_units * 256);
-  rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * g.n_kb)), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
-                                                                              (const uint16_t*)v, kp, vp);
+  rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
+                                                                                    (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  if (mask) {
+    return g.bk == 32 ? launch_sparse_rows<true>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
+                                                 row_counts, order, (uint16_t*)o, o32, lse, st_o, st_ml, st)
+                      : launch_sparse_rows<false>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
+                                                  row_counts, order, (uint16_t*)o, o32, lse, st_o, st_ml, st);
+  }
   const int units = g.n_qb * g.group;
   const RowFilter all = {nullptr, 0, 0, -1, 0};
-  if (mask) {
-    const dim3 grid((unsigned)(units * g.n_kvh));
-    if (!row_counts || g.words <= kWindowMinWords) {
-      if (row_counts) {
-        order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
-        if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-      }
-      attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                    row_counts ? order : nullptr, (uint16_t*)o, o32, lse, all, nullptr,
-                                                    nullptr);
-    } else {
-      // Long rows (more than kLongRow kept blocks) carry most of the work and keep scattered blocks over the
-      // whole sequence: swept independently they miss L2 on most loads.  They are processed one window of
-      // kWindowWords mask words (256 key blocks, 8 MB of K', V' per KV head) at a time, all rows together,
-      // so that the window is served by the L2 of the XCD that owns the KV head and by the memory-side
-      // cache; their accumulators wait in the workspace in between.  Measured at 128K tokens: 218 GB of
-      // L2 fills and 50.7 ms in one sweep per row, 50 GB and 37.3 ms with windows; up to 32K tokens one
-      // sweep is faster.
-      // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
-      order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
-      if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-      for (int w = 0; w < g.words; w += kWindowWords) {
-        const RowFilter lng = {row_counts, kLongRow + 1, 0x7FFFFFFF, w, kWindowWords};
-        attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp,
-                                                      mask, order, (uint16_t*)o, o32, lse, lng, st_o, st_ml);
-        if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-      }
-      const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow, -1, 0};
-      attn_rows_kernel<1><<<grid, dim3(64), 0, st>>>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                    order, (uint16_t*)o, o32, lse, shrt, nullptr, nullptr);
-    }
-  } else {
-    attn_rows_kernel<4><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
-        g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, o32, lse, all, nullptr,
-        nullptr);
-  }
+  attn_rows_kernel<4, false><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
+      g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, o32, lse, all, nullptr,
+      nullptr);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 
@@ -500,7 +565,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
                                 const uint64_t* block_mask, const int32_t* row_counts, void* o, float* lse, void* ws,
                                 size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !block_mask || !o) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomAttention);
+  int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
@@ -510,7 +575,7 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
                                void* ws, size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !o) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomAttention);
+  int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;

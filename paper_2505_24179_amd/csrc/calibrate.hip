@@ -47,14 +47,14 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static CalibWs carve(const sale_params_t* p, void* base) {
   const size_t B = p->batch, Hq = p->n_q_heads, Hkv = p->n_kv_heads, N = p->seq_len;
-  const size_t nq = N / kBlockQ, words = (nq + 63) / 64;
+  const size_t nq = N / kBlockQ, nk = N / (size_t)p->block_k, words = (nk + 63) / 64;
   CalibWs c;
   size_t off = 0;
   auto take = [&](size_t bytes) { uint8_t* ptr = (uint8_t*)base + off; off += align256(bytes); return ptr; };
   c.q4 = take(B * Hq * N * 64);
   c.k4 = take(B * Hkv * N * 64);
   c.qs = (float*)take(B * Hq * nq * 4);
-  c.ks = (float*)take(B * Hkv * nq * 4);
+  c.ks = (float*)take(B * Hkv * nk * 4);
   c.tau = (float*)take(Hq * 4);
   c.o_full = (float*)take(B * Hq * N * kHeadDim * 4);
   c.o_sale = (float*)take(B * Hq * N * kHeadDim * 4);
@@ -79,7 +79,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
                                   float theta, int32_t max_halvings, float* tau_out, float* err_out,
                                   int32_t* halvings_out, void* ws, size_t ws_bytes, void* stream) {
   if (!p || !q || !k || !v || !tau_out) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomAttention);
+  int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   if (!(tau0 > 0.0f && tau0 < 1.0f) || !(theta > 0.0f) || max_halvings < 0 || max_halvings > 64) return SALE_ERR_BAD_SHAPE;
   if (p->n_q_heads > 4096 || p->batch > 4096) return SALE_ERR_UNSUPPORTED;

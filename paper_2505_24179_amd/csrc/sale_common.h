@@ -89,9 +89,9 @@ __device__ __forceinline__ Unit unit_of(const Geo& g, int block, int wave) {
   return u;
 }
 
-// Which geometry a call accepts: any mix of 32 / 64 (quantization), b_q = 64 with b_k = 64 or 32
-// (Selection-Pass), 64 x 64 only (Computation-Pass, calibration).
-enum GeomClass { kGeomQuantize, kGeomSelect, kGeomAttention };
+// Which geometry a call accepts: any mix of 32 / 64 (quantization alone), b_q = 64 with b_k = 64 or 32
+// and at most 4096 key blocks (everything else).
+enum GeomClass { kGeomQuantize, kGeomPath };
 int validate_common(const sale_params_t* p, GeomClass cls);
 // attention launcher shared by the attention entry points and the calibration (attention.hip)
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,

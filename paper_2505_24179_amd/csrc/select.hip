@@ -418,7 +418,7 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
   if (!p || !q || !k || !tau || !block_mask || !row_counts) return SALE_ERR_NULL_ARG;
   const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
   if (!est16 && (!q4 || !k4 || !q_scale || !k_scale)) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomSelect);
+  int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   if (tau_len != 1 && tau_len != p->n_q_heads) return SALE_ERR_BAD_SHAPE;
   const size_t need = sale_workspace_bytes(p, SALE_WS_SELECT);
@@ -443,7 +443,7 @@ extern "C" int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, 
                                      int32_t q_block, int32_t k_block_begin, int32_t k_block_end, int32_t* out,
                                      void* stream) {
   if (!p || !q4 || !k4 || !out) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomSelect);
+  int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   const Geo g = make_geo(p);
   if (q_head < 0 || q_head >= g.n_qh || q_block < 0 || q_block >= g.n_qb) return SALE_ERR_BAD_SHAPE;

@@ -79,9 +79,8 @@ def test_argument_validation_launches_nothing(sale):
     assert lib.sale_dense_attn(ctypes.byref(good.c()), f, f, f, f, None, f, 16, None) == -4
     assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, None, None, f, None, f, 1 << 30, None) == -1
     assert lib.sale_sparse_attn(ctypes.byref(good.c()), f, f, f, f, None, f, None, None, 0, None) == -4
-    p6432 = sale.Params(1, 4, 2, 256, block_k=32)      # the Computation-Pass takes 64 x 64 blocks only
-    assert lib.sale_dense_attn(ctypes.byref(p6432.c()), f, f, f, f, None, f, 1 << 30, None) == -3
-    assert lib.sale_sparse_attn(ctypes.byref(p6432.c()), f, f, f, f, None, f, None, f, 1 << 30, None) == -3
+    assert lib.sale_dense_attn(ctypes.byref(p3232.c()), f, f, f, f, None, f, 1 << 30, None) == -3
+    assert lib.sale_sparse_attn(ctypes.byref(p3232.c()), f, f, f, f, None, f, None, f, 1 << 30, None) == -3
     too_long = sale.Params(1, 1, 1, 64 * 64 * 64 + 64)
     assert lib.sale_dense_attn(ctypes.byref(too_long.c()), f, f, f, f, None, f, 1 << 40, None) == -3
     # calibration
