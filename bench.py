@@ -26,14 +26,14 @@ PEAK_FP6_TFLOPS = 10100.0     # MI355X dense fp6 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
-def cpu_baseline(w, q, k, v, budget_units: int, seed: int = 1234):
+def cpu_baseline(w, q, k, v, budget_units: int, seed: int = 1234, block_k: int = 64, segment: int = 0):
     """Times the CPU oracle (as it stands) on a seeded sample of (head, query
     block) units of the same workload and extrapolates to the whole layer."""
     import numpy as np
     import torch
     from oracle import sale_oracle as so
 
-    geo = so.Geometry(w.seq_len, w.head_dim)
+    geo = so.Geometry(w.seq_len, w.head_dim, 64, block_k, 1, 4, segment=segment)
     rng = np.random.default_rng(seed)
     units = [(int(rng.integers(0, w.n_q_heads)), int(rng.integers(0, geo.n_q))) for _ in range(budget_units)]
     t0 = time.perf_counter()
@@ -42,7 +42,7 @@ def cpu_baseline(w, q, k, v, budget_units: int, seed: int = 1234):
         g = h // w.group
         if g not in cache:           # quantizing K of the group is part of the oracle's work
             kf = k[g].float().numpy()
-            kc, ks = so.quantize_blocks(kf[None], 64)
+            kc, ks = so.quantize_blocks(kf[None], block_k)
             cache = {g: (kf, kc[0], ks[0], v[g].float().numpy())}
         kf, kc, ks, vf = cache[g]
         rs = slice(i * 64, (i + 1) * 64)
@@ -70,6 +70,9 @@ def main() -> int:
     ap.add_argument("--dense-steps", type=int, default=2)
     ap.add_argument("--workload", default="llama31-8b-layer-128k")
     ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--block-k", type=int, default=64, choices=(64, 32),
+                    help="key block size b_k (64: the headline configuration; 32: the paper's shape)")
+    ap.add_argument("--segment-local", action="store_true", help="segment rule for the local area (Appendix C)")
     ap.add_argument("--cpu-units", type=int, default=96, help="oracle sample size (0 = skip the CPU baseline)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -90,7 +93,8 @@ def main() -> int:
     t_gen = time.perf_counter()
     q, k, v = inputs.make_inputs(w)
     t_gen = time.perf_counter() - t_gen
-    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=args.block_k,
+                    flags=sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0)
     dev = torch.device("cuda:0")
     qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
     tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
@@ -141,19 +145,21 @@ def main() -> int:
         torch.cuda.synchronize()
         dense_ms = a.elapsed_time(b) / args.dense_steps
 
-    n_q = p.n_q
-    causal_pairs = w.n_q_heads * n_q * (n_q + 1) // 2
+    # a "pair" is one (query block, key block) tile: 64 x b_k logits
+    n_q, kpq = p.n_q, 64 // args.block_k
+    causal_pairs = w.n_q_heads * sum((i + 1) * kpq for i in range(n_q))
     kept_pairs = int(counts.sum().item())
     density = kept_pairs / causal_pairs
-    flop_pair = 4.0 * 64 * 64 * 128
-    middle_pairs = sum(max(0, i + 1 - p.sink_blocks - p.local_blocks) for i in range(n_q)) * w.n_q_heads
+    flop_pair = 4.0 * 64 * args.block_k * 128
+    # (the segment rule moves at most 3 blocks per row from the middle to the local area: not subtracted)
+    middle_pairs = sum(max(0, (i + 1) * kpq - p.sink_blocks - p.local_blocks) for i in range(n_q)) * w.n_q_heads
     sale_ms = quant_ms + select_ms + sparse_ms
     quant_bytes = (w.n_q_heads + w.n_kv_heads) * w.seq_len * (256 + 64) + (w.n_q_heads + w.n_kv_heads) * n_q * 4
 
     kernels = {
         "quantize": {"bound": "hbm", "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "ms": quant_ms},
-        "select": {"bound": "mfma", "achieved": middle_pairs * 2.0 * 64 * 64 * 128 / (select_ms * 1e-3) / 1e12,
+        "select": {"bound": "mfma", "achieved": middle_pairs * 2.0 * 64 * args.block_k * 128 / (select_ms * 1e-3) / 1e12,
                    "peak": PEAK_FP6_TFLOPS, "unit": "TFLOP/s", "ms": select_ms},
         "sparse_attn": {"bound": "mfma", "achieved": kept_pairs * flop_pair / (sparse_ms * 1e-3) / 1e12,
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "ms": sparse_ms},
@@ -169,7 +175,7 @@ def main() -> int:
     roof.update({"kernel": dominant, "traffic": None})
     # HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (committed summary)
     tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tfile) and args.tau is None:
+    if os.path.exists(tfile) and args.tau is None and args.block_k == 64:
         with open(tfile) as f:
             t = json.load(f).get(dominant)
         if t:
@@ -190,7 +196,8 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "seq_len": w.seq_len, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "block": "64x64", "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
+                   "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local),
+                   "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
                    "seed": w.seed},
         "stages_ms": {"quantize": quant_ms, "select": select_ms, "sparse_attn": sparse_ms, "dense_attn": dense_ms},
         "density": density,
@@ -204,7 +211,8 @@ def main() -> int:
         "input_gen_s": t_gen,
     }
     if args.cpu_units > 0:
-        out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_units)
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_units, block_k=args.block_k,
+                                           segment=4 if args.segment_local else 0)
     print(json.dumps(out))
     return 0
 

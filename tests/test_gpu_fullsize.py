@@ -103,3 +103,57 @@ def test_full_size_sampled_parity(sale, name, n_units):
     print(f"[{name}] borderline mask differences {soft}, max abs err sparse {worst_sparse:.3g} dense {worst_dense:.3g}")
     assert hard == 0
     assert soft <= 4
+
+
+@pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 16), ("llama31-8b-layer-128k", 10)])
+def test_full_size_sampled_parity_paper_shape_64x32(sale, name, n_units):
+    """The same sampled check at the paper's block shape (Sec. 4.1: b_q = 64, b_k = 32) with the segment
+    rule of Appendix C: 18 and 64 mask words, both above the length from which long rows are swept in
+    windows (16 words at b_k = 32)."""
+    w = LONG_ROWS_16K if name == LONG_ROWS_16K.name else inputs.WORKLOADS[name]
+    print(f"\n[{name} 64x32] generating inputs", flush=True)
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=32, flags=sale.FLAG_SEGMENT_LOCAL)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+    tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    mask, counts, m, l = sale.select(p, qd, kd, q4, k4, qs, ks, tau, want_stats=True)
+    o_sparse, lse = sale.sparse_attn(p, qd, kd, vd, mask, counts, want_lse=True)
+    torch.cuda.synchronize()
+    dense_pairs = sum(2 * i + 2 for i in range(p.n_q)) * w.n_q_heads
+    print(f"[{name} 64x32] GPU path done, density {int(counts.sum()) / dense_pairs:.4f}", flush=True)
+
+    geo = so.Geometry(w.seq_len, w.head_dim, 64, 32, 1, 4, segment=4)
+    kq = {}
+    hard = soft = 0
+    worst = 0.0
+    for h, i in _sample_units(w, p.n_q, n_units, seed=(w.seed + 1) & 0xFFFF):
+        g = h // w.group
+        if g not in kq:
+            kf = k[g].float().numpy()
+            kc, oks = so.quantize_blocks(kf[None], 32)
+            kq = {g: (kf, kc[0], oks[0], v[g].float().numpy())}
+            np.testing.assert_array_equal(ks[0, g].cpu().numpy().view(np.uint32), oks[0].view(np.uint32))
+        kf, kc, oks, vf = kq[g]
+        rs = slice(i * 64, (i + 1) * 64)
+        qf = q[h, rs].float().numpy()
+        qc, oqs = so.quantize_blocks(qf[None], 64)
+        jb = max(0, 2 * i - 5)
+        got = sale.qk_int4_products(p, q4, k4, h, i, jb, 2 * i + 2).cpu().numpy()
+        np.testing.assert_array_equal(got, so.int_products(qc[0], kc[jb * 32:(2 * i + 2) * 32]))
+        row, margin, mthr, thr, om, ol = so.select_row(geo, i, qf, kf, qc[0], kc, float(oqs[0, 0]), oks, w.tau)
+        np.testing.assert_allclose(m[0, h, rs].cpu().numpy(), om, rtol=2e-6, atol=2e-6)
+        np.testing.assert_allclose(l[0, h, rs].cpu().numpy(), ol, rtol=2e-5)
+        got_row = words_to_bool(mask[0, h, i].cpu().numpy(), p.n_k)
+        a, b = compare_mask_row(got_row, row, margin, mthr)
+        hard += a; soft += b
+        assert int(counts[0, h, i]) == int(got_row.sum())
+        ref_s, ref_lse = so.attention_block(geo, i, qf, kf, vf, got_row)
+        ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"sparse 64x32 {name} h{h} i{i}")
+        np.testing.assert_allclose(lse[0, h, rs].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
+        worst = max(worst, ms)
+        print(f"[{name} 64x32] unit (h={h}, i={i}) kept {int(got_row.sum())}/{2 * i + 2} ok", flush=True)
+    print(f"[{name} 64x32] borderline mask differences {soft}, max abs err sparse {worst:.3g}")
+    assert hard == 0
+    assert soft <= 4
