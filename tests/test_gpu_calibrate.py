@@ -11,25 +11,27 @@ from paper_2505_24179_amd import inputs
 pytestmark = pytest.mark.gpu
 
 CASES = [
-    (inputs.scaled(inputs.TOY, 1024, 1, 1, "calib-1k"), 0.012, 6),
-    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k"), 0.0064, 6),      # 3, 2, 2 and 0 halvings
-    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-cap"), 1e-6, 3),     # never satisfied: stops at the cap
-    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-loose"), 5.0, 6),    # satisfied at tau0
+    (inputs.scaled(inputs.TOY, 1024, 1, 1, "calib-1k"), 0.012, 6, 64),
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k"), 0.0064, 6, 64),      # 3, 2, 2 and 0 halvings
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-cap"), 1e-6, 3, 64),     # never satisfied: stops at the cap
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-loose"), 5.0, 6, 64),    # satisfied at tau0
+    (inputs.scaled(inputs.LLAMA_32K, 2048, 4, 2, "calib-gqa2-2k-64x32"), 0.0064, 6, 32), # the paper's block shape + segments
 ]
 
 
-@pytest.mark.parametrize("w,theta,max_halvings", CASES, ids=[c[0].name for c in CASES])
-def test_calibration_matches_oracle(w, theta, max_halvings):
+@pytest.mark.parametrize("w,theta,max_halvings,bk", CASES, ids=[c[0].name for c in CASES])
+def test_calibration_matches_oracle(w, theta, max_halvings, bk):
     from paper_2505_24179_amd import sale
     q, k, v = inputs.make_inputs(w)
-    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=bk,
+                    flags=sale.FLAG_SEGMENT_LOCAL if bk == 32 else 0)
     qd, kd, vd = (t.unsqueeze(0).cuda() for t in (q, k, v))
     tau, err, halv = sale.calibrate_tau(p, qd, kd, vd, 0.008, theta, max_halvings)
     tau, err, halv = tau.cpu().numpy(), err.cpu().numpy(), halv.cpu().numpy()
-    geo = so.Geometry(w.seq_len, w.head_dim)
+    geo = so.Geometry(w.seq_len, w.head_dim, 64, bk, 1, 4, segment=4 if bk == 32 else 0)
     qf, kf, vf = q.float().numpy(), k.float().numpy(), v.float().numpy()
     qc, qs = so.quantize_blocks(qf, 64)
-    kc, ks = so.quantize_blocks(kf, 64)
+    kc, ks = so.quantize_blocks(kf, bk)
     skipped = 0
     for h in range(w.n_q_heads):
         g = h // w.group
