@@ -486,7 +486,7 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
 
 // All three in units of 64 keys (scaled by 64 / b_k for a mask with one bit per b_k keys).
 constexpr int kLongRow = 192;        // rows keeping more than this (12K tokens) are swept window by window
-constexpr int kWindowWords = 4;      // window width in mask words of 64 x 64 keys
+constexpr int kWindowWords = 2;      // window width in mask words of 64 x 64 keys: 8K tokens, 4 MB of K', V' per KV head
 constexpr int kWindowMinWords = 8;   // sequences of up to 32K tokens use one sweep per row
 
 namespace {
@@ -509,11 +509,12 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
     return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
   }
   // Long rows carry most of the work and keep scattered blocks over the whole sequence: swept
-  // independently they miss L2 on most loads.  They are processed one window of 16K tokens (8 MB of K', V'
-  // per KV head) at a time, all rows together, so that the window is served by the L2 of the XCD that owns
-  // the KV head and by the memory-side cache; their accumulators wait in the workspace in between.
-  // Measured at 128K tokens: 218 GB of L2 fills and 50.7 ms in one sweep per row, 50 GB and 37.3 ms with
-  // windows; up to 32K tokens one sweep is faster.
+  // independently they miss L2 on most loads.  They are processed one window of 8K tokens (4 MB of K', V'
+  // per KV head: the size of an XCD's L2) at a time, all rows together, so that the window is served by
+  // the L2 of the XCD that owns the KV head; their accumulators wait in the workspace in between.
+  // Measured at 128K tokens (L2 fills / time of the call): one sweep per row 218 GB / 50.7 ms; windows of
+  // 16K tokens 121 GB / 37.5 ms; 8K tokens 57 GB / 37.4 ms; 4K tokens 50 GB / 39.1 ms (the parked state
+  // then costs more than the window saves).  Up to 32K tokens one sweep is faster.
   // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
   for (int w = 0; w < g.words; w += kWindowWords * f) {
     const RowFilter lng = {row_counts, kLongRow * f + 1, 0x7FFFFFFF, w, kWindowWords * f};

@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
     }
     // keys of this block that lie after a query row (only with SALE_FLAG_STATS_CAUSAL)
     const bool mask_diag = g.stats_causal && (j + 1) * g.bk - 1 > u.i * 64;
+    const int ahead = j * g.bk - u.i * 64;      // first key of the block minus first query row
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
       float s[MT * 16];
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float x = acc[mt][nt][r] * rsd;
-          if (mask_diag && (j * g.bk + 32 * mt + mfma32_row(r, lane)) > (u.i * 64 + 32 * nt + c)) x = -INFINITY;
+          if (mask_diag && ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane))) x = -INFINITY;
           s[mt * 16 + r] = x;
           mx = fmaxf(mx, x);
         }
