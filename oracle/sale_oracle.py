@@ -19,7 +19,9 @@ integer products against pure-Python brute force; the hand-derived 4x4-block
 toy; the lossless-grid case of the mask against a library logsumexp; Eq. 3
 against Eq. 4; structural invariants of the mask; attention with every block
 selected against brute-force causal softmax; the renormalisation identity for
-dropped blocks.  No function here is "parity unpinned".
+dropped blocks; the 8-bit Computation-Pass against the unquantized one (exact on
+the 8-bit grid, within the quantization-step bound elsewhere) and the softmax
+invariance of the K smoothing.  No function here is "parity unpinned".
 """
 
 from __future__ import annotations
@@ -35,8 +37,9 @@ QMAX = 7  # symmetric signed 4-bit codes in [-7, 7]; -8 is never produced
 # --------------------------------------------------------------------------
 # Sec. 3.2 "4-bit attention weight approximation": quantization of Q and K
 # --------------------------------------------------------------------------
-def quantize_blocks(x: np.ndarray, block: int):
-    """Per-block symmetric 4-bit quantization (Sec. 3.2; Alg. 1 inputs Q~, K~).
+def quantize_blocks(x: np.ndarray, block: int, qmax: int = QMAX):
+    """Per-block symmetric quantization; 4 bit by default (Sec. 3.2; Alg. 1 inputs Q~, K~),
+    8 bit with qmax = 127 (the quantized Computation-Pass of Sec. 3.4; then read 127 for 7 below).
 
     x      : float32 [H, N, d], values exactly representable in bf16.
     block  : rows per block (b_q for Q, b_k for K); one fp32 scale per
@@ -56,12 +59,12 @@ def quantize_blocks(x: np.ndarray, block: int):
     amax = np.max(np.abs(xb), axis=2).astype(np.float32)            # [H, nb]
     zero = amax == np.float32(0.0)
     safe = np.where(zero, np.float32(1.0), amax).astype(np.float32)
-    seven = np.float32(QMAX)
+    seven = np.float32(qmax)
     scale = np.where(zero, np.float32(1.0), safe / seven).astype(np.float32)
     inv = np.where(zero, np.float32(0.0), seven / safe).astype(np.float32)
     y = (xb * inv[:, :, None]).astype(np.float32)                    # one fp32 multiply
     code = np.rint(y)                                                # ties to even
-    code = np.clip(code, -QMAX, QMAX).astype(np.int8)
+    code = np.clip(code, -qmax, qmax).astype(np.int8)
     return code.reshape(H, N, d), scale
 
 
@@ -286,6 +289,62 @@ def attention_head(geo: Geometry, q, k, v, mask):
         rs = slice(i * bq, (i + 1) * bq)
         o[rs], lse[rs] = attention_block(geo, i, q[rs], k, v, mask[i])
     return o, lse
+
+
+def attention_block_from_scores(geo: Geometry, i: int, s: np.ndarray, v, mask_row):
+    """Eq. 1 for the rows of query block i given their attention weights s [b_q, N] (already divided by
+    sqrt(d)): masks, softmax, product with V.  Returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    n = s.shape[1]
+    rows = i * geo.block_q + np.arange(geo.block_q)
+    cols = np.arange(n)
+    allowed = (cols[None, :] <= rows[:, None]) & np.repeat(np.asarray(mask_row, dtype=bool), geo.block_k)[None, :]
+    s = np.where(allowed, s, -np.inf)
+    mx = s.max(axis=1, keepdims=True)
+    e = np.exp(s - mx)
+    den = e.sum(axis=1, keepdims=True)
+    o = (e / den) @ np.asarray(v, dtype=np.float64)
+    return o, (mx + np.log(den))[:, 0]
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.4 "Integration with SageAttention": the quantized Computation-Pass
+# --------------------------------------------------------------------------
+QMAX8 = 127      # symmetric signed 8-bit codes in [-127, 127]
+BLOCK8 = 64      # rows per quantization block of Q and of K in the Computation-Pass
+
+
+def smooth_k(k: np.ndarray):
+    """The cited 8-bit attention's K smoothing: subtract from every key its head's mean key (per
+    channel, over all N tokens).  Every attention weight of a query row moves by the same amount
+    q . mean, which the softmax of that row cancels, so the result of Eq. 1 is unchanged while the
+    values to quantize get smaller.  k: float32 [H, N, d] -> (k - mean float32 [H, N, d], mean float32
+    [H, d]).  The mean is the exact sum (fp64) divided by N, rounded once to fp32; the subtraction is
+    one fp32 operation."""
+    k = np.asarray(k, dtype=np.float32)
+    mean = (k.astype(np.float64).sum(axis=1) / k.shape[1]).astype(np.float32)
+    return (k - mean[:, None, :]).astype(np.float32), mean
+
+
+def quantize_qk_int8(q: np.ndarray, k: np.ndarray):
+    """Operands of the quantized Computation-Pass: Q per (head, 64-row block) and the smoothed K per
+    (head, 64-row block) in symmetric 8-bit codes with one fp32 scale per block (same arithmetic as
+    quantize_blocks with 127 in place of 7).  q: float32 [Hq, N, d], k: float32 [Hkv, N, d] ->
+    (q_codes int8, q_scale [Hq, N/64], k_codes int8, k_scale [Hkv, N/64], k_mean [Hkv, d])."""
+    ks, mean = smooth_k(k)
+    qc, qs = quantize_blocks(q, BLOCK8, QMAX8)
+    kc, ksc = quantize_blocks(ks, BLOCK8, QMAX8)
+    return qc, qs, kc, ksc, mean
+
+
+def attention_block_int8qk(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_codes, s_k, v, mask_row):
+    """Rows of query block i with the attention weights taken from the 8-bit operands,
+    S = (Q~_i K~^T) s_q s_k[j] / sqrt(d) with K~ the codes of the smoothed K (exact integer products), and the
+    rest of Eq. 1 unchanged: causal and block mask, softmax, product with the unquantized V.
+    q_codes_blk int8 [64, d]; k_codes int8 [N, d]; s_k fp32 [N/64]; mask_row bool [N_k]."""
+    assert geo.block_q == BLOCK8
+    a = int_products(q_codes_blk, k_codes).astype(np.float64)                       # [64, N]
+    s = a * float(s_q_i) * np.repeat(np.asarray(s_k, dtype=np.float64), BLOCK8)[None, :] / math.sqrt(geo.head_dim)
+    return attention_block_from_scores(geo, i, s, v, mask_row)
 
 
 def dense_mask(geo: Geometry) -> np.ndarray:
