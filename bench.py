@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--block-k", type=int, default=64, choices=(64, 32),
                     help="key block size b_k (64: the headline configuration; 32: the paper's shape)")
     ap.add_argument("--segment-local", action="store_true", help="segment rule for the local area (Appendix C)")
+    ap.add_argument("--attn-int8-qk", action="store_true",
+                    help="quantized Computation-Pass (Sec. 3.4): 8-bit Q, K in the first product of sparse AND dense attention")
     ap.add_argument("--cpu-units", type=int, default=96, help="oracle sample size (0 = skip the CPU baseline)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -94,7 +96,8 @@ def main() -> int:
     q, k, v = inputs.make_inputs(w)
     t_gen = time.perf_counter() - t_gen
     p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=args.block_k,
-                    flags=sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0)
+                    flags=(sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0) |
+                          (sale.FLAG_ATTN_INT8_QK if args.attn_int8_qk else 0))
     dev = torch.device("cuda:0")
     qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
     tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
@@ -175,13 +178,19 @@ def main() -> int:
     roof.update({"kernel": dominant, "traffic": None})
     # HBM-side bytes per call measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (committed summary)
     tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(tfile) and args.tau is None and args.block_k == 64:
+    if os.path.exists(tfile) and args.tau is None and args.block_k == 64 and not args.attn_int8_qk:
         with open(tfile) as f:
             t = json.load(f).get(dominant)
         if t:
             roof["traffic"] = {"read_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
                                "source": os.path.relpath(tfile, ROOT)}
 
+    if args.attn_int8_qk:       # the first product runs at the int8 MFMA rate, the second at the bf16 rate
+        for n in ("sparse_attn", "dense_attn"):
+            if n in kernels:
+                kernels[n]["peak"] = 2.0 / (1.0 / PEAK_BF16_TFLOPS + 1.0 / PEAK_INT8_TOPS)
+                kernels[n]["frac"] = kernels[n]["achieved"] / kernels[n]["peak"]
+        roof = dict(kernels[dominant]); roof.pop("ms"); roof.update({"kernel": dominant, "traffic": None})
     out = {
         "metric": "sparse prefill attn ms + speedup vs own dense kernel at 128K; select overhead %",
         "value": sale_ms,
@@ -196,7 +205,7 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "seq_len": w.seq_len, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local),
+                   "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local), "attn_int8_qk": bool(args.attn_int8_qk),
                    "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
                    "seed": w.seed},
         "stages_ms": {"quantize": quant_ms, "select": select_ms, "sparse_attn": sparse_ms, "dense_attn": dense_ms},
@@ -210,7 +219,7 @@ def main() -> int:
         "kernels": kernels,
         "input_gen_s": t_gen,
     }
-    if args.cpu_units > 0:
+    if args.cpu_units > 0 and not args.attn_int8_qk:      # (the CPU leg times the unquantized oracle path)
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_units, block_k=args.block_k,
                                            segment=4 if args.segment_local else 0)
     print(json.dumps(out))

@@ -63,6 +63,13 @@ typedef enum sale_status {
  *   local(i) = local_blocks + max(0, j_last + 1 - sink_blocks - local_blocks) mod 4.
  * They are always kept and feed the statistics like the other local blocks. */
 #define SALE_FLAG_SEGMENT_LOCAL 4u
+/* Quantized Computation-Pass (Sec. 3.4 "Integration with SageAttention"): sale_sparse_attn, sale_dense_attn and
+ * the sparse leg of sale_calibrate_tau take the attention weights from 8-bit operands,
+ *   S = (Q8 K8^T) q_scale8 k_scale8 / sqrt(d),
+ * Q8 / K8 the symmetric codes in [-127, 127] of Q and of K minus its head's mean key, one fp32 scale per
+ * (head, 64-row block), exact integer products; mask, softmax and the product with V (bf16) are unchanged.
+ * The operands are made inside the call (see sale_attn_int8_operands for their definition). */
+#define SALE_FLAG_ATTN_INT8_QK 8u
 
 typedef struct sale_params {
   int32_t batch;
@@ -84,6 +91,7 @@ typedef struct sale_params {
 #define SALE_WS_SPARSE_ATTN 2
 #define SALE_WS_DENSE_ATTN 3
 #define SALE_WS_CALIBRATE 4
+#define SALE_WS_INT8_OPERANDS 5
 
 /* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
  * parameters are invalid). */
@@ -178,6 +186,24 @@ int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, const uint8
                           int32_t q_head, int32_t q_block,
                           int32_t k_block_begin, int32_t k_block_end,
                           int32_t* out, void* stream);
+
+/*
+ * Parity hook: the 8-bit operands of the quantized Computation-Pass (SALE_FLAG_ATTN_INT8_QK), made by the
+ * kernels the attention calls use.  Per KV head, k_mean[c] = fp32(exact sum over the N keys of channel c / N);
+ * K' = K - k_mean in fp32; then for every 64-row block of a Q head (of K' of a KV head), in IEEE fp32:
+ *   amax = max|x|; scale = amax / 127; code = clamp(rint(x * (127 / amax)), -127, 127)
+ * (round half to even; an all-zero block gets scale 1 and codes 0).
+ *
+ *   q8        out: int8 [batch][n_q_heads ][N][d]
+ *   k8        out: int8 [batch][n_kv_heads][N][d]
+ *   q_scale8  out: fp32 [batch][n_q_heads ][N / 64]
+ *   k_scale8  out: fp32 [batch][n_kv_heads][N / 64]
+ *   k_mean    out: fp32 [batch][n_kv_heads][d]
+ *   ws           : workspace of sale_workspace_bytes(p, SALE_WS_INT8_OPERANDS) bytes
+ */
+int sale_attn_int8_operands(const sale_params_t* p, const void* q, const void* k,
+                            int8_t* q8, int8_t* k8, float* q_scale8, float* k_scale8, float* k_mean,
+                            void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Per-head threshold calibration (Sec. 3.3).  For every query head, starting from tau0 (the paper uses

@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsale.so")
-SOURCES = ["api.hip", "quantize.hip", "select.hip", "attention.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "quantize.hip", "quantize8.hip", "select.hip", "attention.hip", "calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
@@ -37,7 +37,7 @@ def _compile(src: str, extra) -> str:
 
 
 def build(extra_flags=(), verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -10,7 +10,7 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
   if (p->n_q_heads % p->n_kv_heads != 0) return SALE_ERR_BAD_SHAPE;
   if (p->sink_blocks < 0 || p->local_blocks < 1) return SALE_ERR_BAD_SHAPE;
   if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
-  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL)) return SALE_ERR_UNSUPPORTED;
+  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL | SALE_FLAG_ATTN_INT8_QK)) return SALE_ERR_UNSUPPORTED;
   if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
   if (cls != kGeomQuantize) {
     if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
@@ -54,10 +54,14 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
     case SALE_WS_DENSE_ATTN:
       // K and V copied once into MFMA fragment order, parked row state (fp32 O^T accumulators and
       // max / sum per lane: 33 KB per 64-row block) and the order in which rows are issued
+      // (+ the 8-bit operand copies of the quantized Computation-Pass)
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
-             (rows / kBlockQ) * (sizeof(int32_t) + 2048 * 16 + 256 * 4);
+             (rows / kBlockQ) * (sizeof(int32_t) + 2048 * 16 + 256 * 4) +
+             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0);
     case SALE_WS_CALIBRATE:
       return calibrate_workspace_bytes(p);
+    case SALE_WS_INT8_OPERANDS:
+      return (size_t)p->batch * p->n_kv_heads * (p->seq_len / 64) * 128 * sizeof(double);
     default:
       return 0;
   }

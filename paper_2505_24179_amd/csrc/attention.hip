@@ -109,10 +109,18 @@ struct RowFilter {
 // BK32: the mask has one bit per 32 keys (b_k = 32) instead of one per 64.  The kernel always works on
 // pairs of 32-key half-tiles; with b_k = 64 a pair is the two halves of one block, with b_k = 32 it is any
 // two kept half-tiles of the row (the operand copies K', V' are addressable by half-tile).
-template <int WAVES, bool BK32>
+// QK8: the first product runs on the 8-bit operands of the quantized Computation-Pass (Sec. 3.4 "Integration
+// with SageAttention") with v_mfma_i32_32x32x32_i8: half the K bytes and half the MFMA time of that product.
+struct Qk8 {
+  const int8_t* q8;       // [q head][N][128]
+  const u32x4* k8p;       // fragment order, 8 KB per 64 keys
+  const float* q_scale;   // [q head][N / 64]
+  const float* k_scale;   // [kv head][N / 64]
+};
+template <int WAVES, bool BK32, bool QK8>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
                                                                const bf16x8* __restrict__ kp,
-                                                               const bf16x8* __restrict__ vp,
+                                                               const bf16x8* __restrict__ vp, Qk8 q8o,
                                                                const uint64_t* __restrict__ mask,
                                                                const int32_t* __restrict__ order,
                                                                uint16_t* __restrict__ o, float* __restrict__ o32,
@@ -154,23 +162,51 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 
   // ---- operands -----------------------------------------------------------------------
   // Q fragments (B operand of S^T = K Q^T), resident for the whole row.
-  bf16x8 qf[2][8];
+  bf16x8 qf[QK8 ? 1 : 2][QK8 ? 1 : 8];
+  i32x4 qf8[QK8 ? 2 : 1][QK8 ? 4 : 1];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
-    const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+    if constexpr (QK8) {
+      const int8_t* row = q8o.q8 + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 16 * h;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
+      for (int s = 0; s < 4; ++s) qf8[nt][s] = *(const i32x4*)(row + 32 * s);
+    } else {
+      const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
+    }
+  }
+  const float cs = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(d)
+  // Logits are handled in log2 units: x = (raw product) * cl[slot], cl = log2(e) / sqrt(d), times the
+  // scales of the 8-bit operands of the slot's key block when QK8.
+  float cl[2] = {cs, cs};
+  float ks_pend[2] = {1.0f, 1.0f};      // QK8: K scale of the half-tile whose operands were requested last
+  float sq_cs = cs;
+  const i32x4* k8t = nullptr;
+  const float* ks8 = nullptr;
+  if constexpr (QK8) {
+    sq_cs = q8o.q_scale[unit_flat] * cs;
+    k8t = (const i32x4*)q8o.k8p + (size_t)u.kvh * g.seq * 8 + lane;     // 512 16-byte chunks per 64 keys
+    ks8 = q8o.k_scale + (size_t)u.kvh * (g.seq / 64);
   }
   const bf16x8* kt = kp + (size_t)u.kvh * g.seq * 16 + lane;     // 1024 16-byte chunks per 64 keys
   const bf16x8* vt = vp + (size_t)u.kvh * g.seq * 16 + lane;
   // Work proceeds in pairs of 32-key half-tiles held in slots 0 and 1; half-tile hb covers keys
   // 32hb .. 32hb+31 (half hb % 2 of the 64-key tile hb / 2 of K', V').  K operands of slot mt: kf[mt][s];
   // V operands of slot mt: vf[mt][dt][s2].
-  bf16x8 kf[2][8], vf[2][4][2];
+  bf16x8 kf[QK8 ? 1 : 2][QK8 ? 1 : 8], vf[2][4][2];
+  i32x4 kf8[QK8 ? 2 : 1][QK8 ? 4 : 1];
   auto load_k = [&](int hb, int mt) __attribute__((always_inline)) {
-    const bf16x8* t = kt + (size_t)hb * 512;
+    if constexpr (QK8) {
+      const i32x4* t = k8t + (size_t)hb * 256;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) kf[mt][s] = t[s * 64];
+      for (int s = 0; s < 4; ++s) kf8[mt][s] = t[s * 64];
+      ks_pend[mt] = ks8[hb >> 1];
+    } else {
+      const bf16x8* t = kt + (size_t)hb * 512;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) kf[mt][s] = t[s * 64];
+    }
   };
   auto load_v = [&](int hb, int mt) __attribute__((always_inline)) {
     const bf16x8* t = vt + (size_t)(hb >> 1) * 1024 + (hb & 1) * 128;
@@ -187,8 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[dt][nt][r] = 0.0f;
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
-  const float cs = 0.08838834764831845f * 1.4426950408889634f;   // log2(e) / sqrt(d)
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};      // m_run in log2 units
 
   if (resume) {
     const f32x4* so = st_o + unit_flat * 2048 + lane;       // [dt][nt][quarter][lane] 16-byte chunks
@@ -229,14 +264,28 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   bf16x8 P[2][2][2];
 
   auto qk_half = [&](int mt) __attribute__((always_inline)) {                       // S[mt][*] = K(half mt) Q^T
+    if constexpr (QK8) {
+      i32x16 a0 = {0}, a1 = {0};
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+      for (int s = 0; s < 4; ++s) {
+        a0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf8[mt][s], qf8[0][s], a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf8[mt][s], qf8[1][s], a1, 0, 0, 0);
+      }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) S[mt][nt][r] = 0.0f;
+      for (int r = 0; r < 16; ++r) {
+        S[mt][0][r] = (float)a0[r];
+        S[mt][1][r] = (float)a1[r];
+      }
+    } else {
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      S[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[0][s], S[mt][0], 0, 0, 0);
-      S[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[1][s], S[mt][1], 0, 0, 0);
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[mt][nt][r] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        S[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[0][s], S[mt][0], 0, 0, 0);
+        S[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[mt][s], qf[1][s], S[mt][1], 0, 0, 0);
+      }
     }
   };
   auto pv_half = [&](int mt) __attribute__((always_inline)) {                       // O^T += V^T(half mt) P^T(half mt)
@@ -265,7 +314,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
       float v = fmaxf(S[mt][nt][0], S[mt][nt][1]);
 #pragma unroll
       for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[mt][nt][r]), S[mt][nt][r + 1]);
-      mx[nt] = max_with_other_half(v);
+      mx[nt] = max_with_other_half(v) * cl[mt];
     }
   };
   // Lazy rescale: O and l are rescaled only when some row's maximum grew (exact: otherwise the factor
@@ -275,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) {
         const float m_new = fmaxf(m_run[nt], mx[nt]);
-        float alpha = __builtin_amdgcn_exp2f((m_run[nt] - m_new) * cs);
+        float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
         // b_k = 32: a query row may have seen no key yet (its first half-tile lies above the diagonal)
         if constexpr (BK32) alpha = m_new == -INFINITY ? 1.0f : alpha;
         l_run[nt] *= alpha;
@@ -299,7 +348,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      const float mb = (BK32 && m_run[nt] == -INFINITY) ? 0.0f : m_run[nt] * cs;
+      const float mb = (BK32 && m_run[nt] == -INFINITY) ? 0.0f : m_run[nt];
+      const float ch = cl[mt];
       float sum = l_run[nt];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
@@ -308,8 +358,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
         for (int e2 = 0; e2 < 4; ++e2) {
           const int r = 8 * s2 + 2 * e2;
           bf16x2 pk;
-          pk[0] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r] * cs - mb);
-          pk[1] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r + 1] * cs - mb);
+          pk[0] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r] * ch - mb);
+          pk[1] = (__bf16)__builtin_amdgcn_exp2f(S[mt][nt][r + 1] * ch - mb);
           sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);   // row sum of the rounded P
           packed[e2] = __builtin_bit_cast(unsigned, pk);
         }
@@ -337,6 +387,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     qk_half(1);
     exp_half(0);
     // stage C
+    if constexpr (QK8) cl[1] = ks_pend[1] * sq_cs;      // scale of slot 1's key block, requested a step ago
     pv_half(0);
     max_half(1, diag);
     if constexpr (!kLast) { load_k(nxt.b, 1); load_v(nxt.a, 0); }
@@ -347,6 +398,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     if constexpr (!kLast) qk_half(0);
     exp_half(1);
     if constexpr (!kLast) { SALE_PIPE(16, 6, 0) }
+    if constexpr (QK8 && !kLast) cl[0] = ks_pend[0] * sq_cs;      // slot 0 now holds the next pair's first half-tile
   };
   const auto T = std::true_type{};
   const auto F = std::false_type{};
@@ -396,6 +448,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     load_k(pc.b, 1);
     load_v(pc.a, 0);
     qk_half(0);
+    if constexpr (QK8) cl[0] = ks_pend[0] * sq_cs;
     bool has_next = next_pair(pn);
     set_koff(pc, lone_first);
     if (!has_next) {
@@ -457,7 +510,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
           *(bf16x4*)(orow + 32 * dt + 8 * q4) = w;
         }
       }
-    if (lse && h == 0) lse[row] = l_tot > 0.0f ? m_run[nt] * 0.08838834764831845f + __logf(l_tot) : -INFINITY;
+    if (lse && h == 0) lse[row] = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(l_tot) : -INFINITY;
   }
 }
 
@@ -491,8 +544,8 @@ constexpr int kWindowMinWords = 8;   // sequences of up to 32K tokens use one sw
 
 namespace {
 
-template <bool BK32>
-int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, const uint64_t* mask,
+template <bool BK32, bool QK8>
+int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, Qk8 q8o, const uint64_t* mask,
                        const int32_t* row_counts, int32_t* order, uint16_t* o, float* o32, float* lse, f32x4* st_o,
                        float* st_ml, hipStream_t st) {
   const int units = g.n_qb * g.group;
@@ -504,8 +557,8 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
   if (!row_counts || g.words <= kWindowMinWords * f) {
-    attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, row_counts ? order : nullptr, o, o32, lse, all,
-                                                        nullptr, nullptr);
+    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, o, o32,
+                                                             lse, all, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
   }
   // Long rows carry most of the work and keep scattered blocks over the whole sequence: swept
@@ -518,11 +571,12 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
   for (int w = 0; w < g.words; w += kWindowWords * f) {
     const RowFilter lng = {row_counts, kLongRow * f + 1, 0x7FFFFFFF, w, kWindowWords * f};
-    attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, order, o, o32, lse, lng, st_o, st_ml);
+    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, o, o32, lse, lng, st_o, st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
   const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow * f, -1, 0};
-  attn_rows_kernel<1, BK32><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, mask, order, o, o32, lse, shrt, nullptr, nullptr);
+  attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, o, o32, lse, shrt, nullptr,
+                                                           nullptr);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 
@@ -544,17 +598,38 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
                                                                                     (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  const bool qk8 = (p->flags & SALE_FLAG_ATTN_INT8_QK) != 0;
+  Qk8 q8o = {nullptr, nullptr, nullptr, nullptr};
+  if (qk8) {
+    // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
+    const uintptr_t end = (uintptr_t)(order + n_units);
+    const Int8Operands w = carve_int8_operands(p, (void*)((end + 63) & ~(uintptr_t)63));
+    const int rc = launch_int8_operands(p, q, k, w, true, st);
+    if (rc != SALE_OK) return rc;
+    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale};
+  }
+  const uint16_t* qq = (const uint16_t*)q;
+  const bf16x8 *kpp = (const bf16x8*)kp, *vpp = (const bf16x8*)vp;
   if (mask) {
-    return g.bk == 32 ? launch_sparse_rows<true>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                 row_counts, order, (uint16_t*)o, o32, lse, st_o, st_ml, st)
-                      : launch_sparse_rows<false>(g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, mask,
-                                                  row_counts, order, (uint16_t*)o, o32, lse, st_o, st_ml, st);
+    if (g.bk == 32)
+      return qk8 ? launch_sparse_rows<true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse, st_o,
+                                                  st_ml, st)
+                 : launch_sparse_rows<true, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse,
+                                                   st_o, st_ml, st);
+    return qk8 ? launch_sparse_rows<false, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse, st_o,
+                                                 st_ml, st)
+               : launch_sparse_rows<false, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse,
+                                                  st_o, st_ml, st);
   }
   const int units = g.n_qb * g.group;
   const RowFilter all = {nullptr, 0, 0, -1, 0};
-  attn_rows_kernel<4, false><<<dim3((unsigned)(((units + 3) / 4) * g.n_kvh)), dim3(256), 0, st>>>(
-      g, (const uint16_t*)q, (const bf16x8*)kp, (const bf16x8*)vp, nullptr, nullptr, (uint16_t*)o, o32, lse, all, nullptr,
-      nullptr);
+  const dim3 grid((unsigned)(((units + 3) / 4) * g.n_kvh));
+  if (qk8)
+    attn_rows_kernel<4, false, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, (uint16_t*)o, o32, lse,
+                                                                all, nullptr, nullptr);
+  else
+    attn_rows_kernel<4, false, false><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, (uint16_t*)o, o32,
+                                                                 lse, all, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 

@@ -99,4 +99,18 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
 Geo make_geo(const sale_params_t* p);
 size_t calibrate_workspace_bytes(const sale_params_t* p);
 
+// 8-bit operands of the quantized Computation-Pass (quantize8.hip).
+struct Int8Operands {
+  int8_t* q8;        // [q head][N][128] codes, row-major
+  int8_t* k8;        // codes of the smoothed K: MFMA fragment order (attention) or row-major (parity hook)
+  float* q_scale;    // [q head][N / 64]
+  float* k_scale;    // [kv head][N / 64]
+  float* k_mean;     // [kv head][128]
+  double* partial;   // [kv head][N / 64][128] column sums per tile
+};
+size_t int8_operand_bytes(const sale_params_t* p);
+Int8Operands carve_int8_operands(const sale_params_t* p, void* base);
+int launch_int8_operands(const sale_params_t* p, const void* q, const void* k, const Int8Operands& w, bool frag_k,
+                         hipStream_t st);
+
 }  // namespace sale

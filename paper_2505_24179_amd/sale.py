@@ -23,10 +23,12 @@ OK = 0
 FLAG_STATS_CAUSAL = 1
 FLAG_SELECT_16BIT = 2
 FLAG_SEGMENT_LOCAL = 4
+FLAG_ATTN_INT8_QK = 8
 WS_SELECT = 1
 WS_SPARSE_ATTN = 2
 WS_DENSE_ATTN = 3
 WS_CALIBRATE = 4
+WS_INT8_OPERANDS = 5
 
 
 class _Params(ctypes.Structure):
@@ -75,6 +77,7 @@ _SIGS = {
     "sale_sparse_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "sale_attn_int8_operands": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_calibrate_tau": (ctypes.c_int, [_pp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float, _i32, _vp, _vp, _vp,
                                           _vp, _sz, _vp]),
 }
@@ -181,6 +184,21 @@ def qk_int4_products(p: Params, q4, k4, q_head: int, q_block: int, k_block_begin
     _check(_lib.sale_qk_int4_products(ctypes.byref(p.c()), _ptr(q4), _ptr(k4), q_head, q_block,
                                       k_block_begin, k_block_end, _ptr(out), _stream()))
     return out
+
+
+def attn_int8_operands(p: Params, q, k):
+    """-> (q8 int8 [B,Hq,N,d], k8 int8 [B,Hkv,N,d], q_scale8 f32 [B,Hq,N/64], k_scale8 f32 [B,Hkv,N/64],
+    k_mean f32 [B,Hkv,d]): the 8-bit operands of the quantized Computation-Pass (parity hook)."""
+    dev = q.device
+    q8 = torch.empty(p.batch, p.n_q_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
+    k8 = torch.empty(p.batch, p.n_kv_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
+    qs = torch.empty(p.batch, p.n_q_heads, p.seq_len // 64, dtype=torch.float32, device=dev)
+    ks = torch.empty(p.batch, p.n_kv_heads, p.seq_len // 64, dtype=torch.float32, device=dev)
+    mean = torch.empty(p.batch, p.n_kv_heads, p.head_dim, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(1, workspace_bytes(p, WS_INT8_OPERANDS)), dtype=torch.uint8, device=dev)
+    _check(_lib.sale_attn_int8_operands(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q8), _ptr(k8), _ptr(qs), _ptr(ks),
+                                        _ptr(mean), _ptr(ws), ws.numel(), _stream()))
+    return q8, k8, qs, ks, mean
 
 
 def calibrate_tau(p: Params, q, k, v, tau0: float = 0.008, theta: float = 0.4, max_halvings: int = 8, ws=None):

@@ -157,3 +157,52 @@ def test_full_size_sampled_parity_paper_shape_64x32(sale, name, n_units):
     print(f"[{name} 64x32] borderline mask differences {soft}, max abs err sparse {worst:.3g}")
     assert hard == 0
     assert soft <= 4
+
+
+@pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 12), ("llama31-8b-layer-128k", 8)])
+def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
+    """The quantized Computation-Pass (Sec. 3.4 "Integration with SageAttention") at full size, windowed sweep
+    included: sampled units against the oracle that takes the same 8-bit operands."""
+    w = LONG_ROWS_16K if name == LONG_ROWS_16K.name else inputs.WORKLOADS[name]
+    print(f"\n[{name} int8] generating inputs", flush=True)
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=sale.FLAG_ATTN_INT8_QK)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+    tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+    ws = torch.empty(sale.workspace_bytes(p, sale.WS_SPARSE_ATTN), dtype=torch.uint8, device=dev)
+    o_sparse, lse = sale.sparse_attn(p, qd, kd, vd, mask, counts, want_lse=True, ws=ws)
+    o_sparse = o_sparse.clone()
+    o_dense, _ = sale.dense_attn(p, qd, kd, vd, ws=ws)
+    q8, k8, qs8, ks8, mean = sale.attn_int8_operands(p, qd, kd)
+    torch.cuda.synchronize()
+    print(f"[{name} int8] GPU path done", flush=True)
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    kq = {}
+    worst_s = worst_d = 0.0
+    for h, i in _sample_units(w, p.n_q, n_units, seed=(w.seed + 2) & 0xFFFF):
+        g = h // w.group
+        if g not in kq:
+            kf = k[g].float().numpy()
+            ksm, omean = so.smooth_k(kf[None])
+            kc, oks = so.quantize_blocks(ksm, 64, 127)
+            np.testing.assert_array_equal(mean[0, g].cpu().numpy().view(np.uint32), omean[0].view(np.uint32))
+            np.testing.assert_array_equal(k8[0, g].cpu().numpy(), kc[0])
+            np.testing.assert_array_equal(ks8[0, g].cpu().numpy().view(np.uint32), oks[0].view(np.uint32))
+            kq = {g: (kc[0], oks[0], v[g].float().numpy())}
+        kc, oks, vf = kq[g]
+        rs = slice(i * 64, (i + 1) * 64)
+        qc, oqs = so.quantize_blocks(q[h, rs].float().numpy()[None], 64, 127)
+        np.testing.assert_array_equal(q8[0, h, rs].cpu().numpy(), qc[0])
+        assert qs8[0, h, i].cpu().numpy().view(np.uint32) == oqs[0, 0].view(np.uint32)
+        got_row = words_to_bool(mask[0, h, i].cpu().numpy(), p.n_k)
+        ref_s, ref_lse = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, got_row)
+        ref_d, _ = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, np.arange(geo.n_k) <= i)
+        ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"int8 sparse {name} h{h} i{i}")
+        md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"int8 dense {name} h{h} i{i}")
+        np.testing.assert_allclose(lse[0, h, rs].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
+        worst_s, worst_d = max(worst_s, ms), max(worst_d, md)
+        print(f"[{name} int8] unit (h={h}, i={i}) kept {int(got_row.sum())}/{i + 1} ok", flush=True)
+    print(f"[{name} int8] max abs err sparse {worst_s:.3g} dense {worst_d:.3g}")
