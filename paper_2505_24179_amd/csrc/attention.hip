@@ -397,7 +397,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     // stage D (kf[0] of the next pair was requested before stage A)
     if constexpr (!kLast) qk_half(0);
     exp_half(1);
-    if constexpr (!kLast) { SALE_PIPE(16, 6, 0) }
+    if constexpr (!kLast) {
+      if constexpr (QK8) { SALE_PIPE(8, 14, 0) } else { SALE_PIPE(16, 6, 0) }      // 8 MFMAs in the 8-bit first product
+    }
     if constexpr (QK8 && !kLast) cl[0] = ks_pend[0] * sq_cs;      // slot 0 now holds the next pair's first half-tile
   };
   const auto T = std::true_type{};
