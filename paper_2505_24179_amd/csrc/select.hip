@@ -37,7 +37,7 @@ template <int MT>
 __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                     const float* __restrict__ tau, int tau_len, float* __restrict__ thr,
                                                     float* __restrict__ m_out, float* __restrict__ l_out) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform by construction
   const Unit u = unit_of(g, blockIdx.x, wave);
   if (!u.valid) return;
   const int c = lane & 31, h = lane >> 5;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float x = acc[mt][nt][r] * rsd;
-          if (mask_diag && ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane))) x = -INFINITY;
+          x = (mask_diag & (ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane)))) ? -INFINITY : x;
           s[mt * 16 + r] = x;
           mx = fmaxf(mx, x);
         }
@@ -217,7 +217,7 @@ __device__ __forceinline__ float lane_max(const f32x16 acc[MT][2], int nt) {
 }
 
 // One wave scores HPW query heads of one GQA group at the same query block, so every K~ fragment it
-// loads feeds HPW x 2 MFMAs.  A workgroup is 4 such waves (consecutive head sets / query blocks of one
+// loads feeds HPW x 2 MFMAs (HPW = 4 when the group allows: 14.6 against 15.3 ms at 128K with 64-key blocks).  A workgroup is 4 such waves (consecutive head sets / query blocks of one
 // KV head); workgroups go round-robin over KV heads, longest rows first.
 // (At least 2 waves per SIMD caps the register file at 256 VGPRs, which lets the MFMA results land in
 // ordinary VGPRs instead of AGPRs that the max chain would have to copy out one by one.)
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
     Geo g, const uint8_t* __restrict__ q6, const uint8_t* __restrict__ k6, const float* __restrict__ q_scale,
     const float* __restrict__ k_scale, const float* __restrict__ thr, uint64_t* __restrict__ mask,
     int32_t* __restrict__ row_counts) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform by construction
   const int c = lane & 31;
   const int sets = g.group / HPW;                 // head sets per (KV head, query block)
   const int units = g.n_qb * sets;
@@ -296,7 +296,7 @@ template <int MT>
 __global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                        const float* __restrict__ thr, uint64_t* __restrict__ mask,
                                                        int32_t* __restrict__ row_counts) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform by construction
   const Unit u = unit_of(g, blockIdx.x, wave);
   if (!u.valid) return;
   const int c = lane & 31, h = lane >> 5;
@@ -399,6 +399,10 @@ int launch_select(const Geo& g, bool est16, const void* q, const void* k, const 
   if (est16) {
     select16_kernel<MT><<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, (const uint16_t*)q, (const uint16_t*)k,
                                                                                 thr_c, block_mask, row_counts);
+  } else if (MT == 2 && g.group % 4 == 0) {     // (with 32-key blocks two heads per wave are faster: 15.8 against 17.1 ms at 128K)
+    const int t4 = (g.n_qb * (g.group / 4) + 3) / 4;
+    select_kernel<4, MT><<<dim3((unsigned)(t4 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr_c,
+                                                                              block_mask, row_counts);
   } else if (g.group % 2 == 0) {
     const int t2 = (g.n_qb * (g.group / 2) + 3) / 4;
     select_kernel<2, MT><<<dim3((unsigned)(t2 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr_c,
