@@ -2,7 +2,7 @@
 chosen (by bisection on the GPU mask) to give about 5, 10, 20, 40 and 60 % kept
 blocks; at every point the mask and the sparse output of sampled (head, query
 block) units are checked against the oracle and density, stage times and errors
-are printed (the table in the design doc comes from this test's output)."""
+are printed."""
 import numpy as np
 import pytest
 import torch
