@@ -123,6 +123,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
                                                                const bf16x8* __restrict__ vp, Qk8 q8o,
                                                                const uint64_t* __restrict__ mask,
                                                                const int32_t* __restrict__ order,
+                                                               const int32_t* __restrict__ assign,
                                                                uint16_t* __restrict__ o, float* __restrict__ o32,
                                                                float* __restrict__ lse,
                                                                RowFilter flt, f32x4* __restrict__ st_o,
@@ -135,7 +136,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     u.kvh = blockIdx.x % g.n_kvh;
     const int rank = (blockIdx.x / g.n_kvh) * WAVES + wave;
     u.valid = rank < units;
-    const int id = !u.valid ? 0 : (order ? order[(size_t)u.kvh * units + rank] : units - 1 - rank);
+    int id = !u.valid ? 0 : (order ? order[(size_t)u.kvh * units + rank] : units - 1 - rank);
+    if (assign) {
+      // balanced issue: slot `rank` of lane blockIdx % n_kvh holds a unit of ANY KV head (or nothing)
+      const int entry = u.valid ? assign[(size_t)u.kvh * units + rank] : -1;
+      u.valid = entry >= 0;
+      u.kvh = u.valid ? entry / units : 0;
+      id = u.valid ? entry % units : 0;
+    }
     u.i = id / g.group;
     u.qh = u.kvh * g.group + id % g.group;
   }
@@ -540,6 +548,100 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
 }
 
 // All three in units of 64 keys (scaled by 64 / b_k for a mask with one bit per b_k keys).
+// Workgroups go to the XCDs round-robin, so "lane" blockIdx % n_kvh of a launch always runs on the same XCDs.
+// With lane = KV head an XCD's L2 serves one head's K', V', but the heads of a layer keep very different
+// numbers of blocks (1.6x between the lightest and the heaviest at 128K here) and the light XCDs would idle.
+// This table moves a representative sample (every so-many-th of the sorted list) of the units of every
+// over-loaded head to the lanes of the under-loaded ones, in proportion to what they lack:
+// assign[lane][slot] = kvh * units + unit id, or -1.  Units with count <= min_count do not take part.
+// One workgroup.  Falls back to lane = KV head when there are too many lanes or a lane would overflow.
+constexpr int kMaxLanes = 256;
+__global__ __launch_bounds__(1024) void balance_kernel(Geo g, const int32_t* __restrict__ row_counts,
+                                                       const int32_t* __restrict__ order, int min_count,
+                                                       int32_t* __restrict__ assign) {
+  __shared__ int n_in[kMaxLanes], n_shed[kMaxLanes], shed_off[kMaxLanes], recv_lo[kMaxLanes + 1];
+  __shared__ unsigned long long work[kMaxLanes];
+  const int units = g.n_qb * g.group, lanes = g.n_kvh;
+  const int total = lanes * units;
+  auto count_of = [&](int h, int id) {
+    return row_counts[(size_t)(h * g.group + id % g.group) * g.n_qb + id / g.group];
+  };
+  for (int e = threadIdx.x; e < total; e += blockDim.x) assign[e] = -1;
+  for (int h = threadIdx.x; h < min(lanes, kMaxLanes); h += blockDim.x) { n_in[h] = 0; work[h] = 0; }
+  __syncthreads();
+  const bool balance = lanes <= kMaxLanes && lanes > 1;
+  if (balance) {      // every thread sums a contiguous piece (mostly one head) and adds it once per head
+    const int per = (total + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int e0 = threadIdx.x * per, e1 = min(e0 + per, total);
+    int h_run = -1, n_run = 0;
+    unsigned long long w_run = 0;
+    for (int e = e0; e < e1; ++e) {
+      const int h = e / units, c = count_of(h, e % units);
+      if (h != h_run) {
+        if (n_run) { atomicAdd(&n_in[h_run], n_run); atomicAdd(&work[h_run], w_run); }
+        h_run = h; n_run = 0; w_run = 0;
+      }
+      if (c > min_count) { ++n_run; w_run += (unsigned long long)c; }
+    }
+    if (n_run) { atomicAdd(&n_in[h_run], n_run); atomicAdd(&work[h_run], w_run); }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (balance) {
+      unsigned long long sum = 0;
+      for (int h = 0; h < lanes; ++h) sum += work[h];
+      const double target = (double)sum / lanes;
+      double lack_total = 0.0;
+      int shed_total = 0;
+      for (int h = 0; h < lanes; ++h) {
+        const double w = (double)work[h];
+        n_shed[h] = w > target ? (int)((double)n_in[h] * (w - target) / w) : 0;
+        shed_off[h] = shed_total;
+        shed_total += n_shed[h];
+        if (w < target) lack_total += target - w;
+      }
+      // the shed units, numbered shed_off[h] + k, go to the lanes that lack work, in proportion
+      double lack_run = 0.0;
+      bool ok = true;
+      for (int l = 0; l < lanes; ++l) {
+        recv_lo[l] = lack_total > 0.0 ? (int)((double)shed_total * (lack_run / lack_total)) : 0;
+        const double w = (double)work[l];
+        if (w < target) lack_run += target - w;
+      }
+      recv_lo[lanes] = shed_total;
+      for (int l = 0; l < lanes; ++l) ok = ok && (n_in[l] - n_shed[l] + recv_lo[l + 1] - recv_lo[l] <= units);
+      if (!ok || lack_total <= 0.0) {
+        for (int h = 0; h < lanes; ++h) { n_shed[h] = 0; shed_off[h] = 0; }
+        for (int l = 0; l <= lanes; ++l) recv_lo[l] = 0;
+      }
+    }
+  }
+  __syncthreads();
+  // order[h][r], r < n_in[h], are the participating units of head h, longest first
+  for (int e = threadIdx.x; e < total; e += blockDim.x) {
+    const int h = e / units, r = e % units;
+    const int id = order[(size_t)h * units + r];
+    if (count_of(h, id) <= min_count) continue;
+    int lane = h, pos = r;
+    if (balance) {
+      const long long ns = n_shed[h], n = n_in[h];
+      const int before = (int)((long long)r * ns / n), upto = (int)((long long)(r + 1) * ns / n);
+      if (upto > before) {                      // this unit is shed: global shed number p
+        const int p = shed_off[h] + before;
+        int l = 0;
+        while (l + 1 < lanes && recv_lo[l + 1] <= p) ++l;
+        lane = l;
+        // Received units go first in their new lane: all lanes then read the shedding head's window at the
+        // start of a launch, together (interleaving them with the lane's own units was 6 % slower).
+        pos = p - recv_lo[l];
+      } else {
+        pos = (recv_lo[h + 1] - recv_lo[h]) + (r - before);
+      }
+    }
+    assign[(size_t)lane * units + pos] = h * units + id;
+  }
+}
+
 constexpr int kLongRow = 192;        // rows keeping more than this (12K tokens) are swept window by window
 constexpr int kWindowWords = 2;      // window width in mask words of 64 x 64 keys: 8K tokens, 4 MB of K', V' per KV head
 constexpr int kWindowMinWords = 8;   // sequences of up to 32K tokens use one sweep per row
@@ -548,8 +650,8 @@ namespace {
 
 template <bool BK32, bool QK8>
 int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, Qk8 q8o, const uint64_t* mask,
-                       const int32_t* row_counts, int32_t* order, uint16_t* o, float* o32, float* lse, f32x4* st_o,
-                       float* st_ml, hipStream_t st) {
+                       const int32_t* row_counts, int32_t* order, int32_t* assign, uint16_t* o, float* o32, float* lse,
+                       f32x4* st_o, float* st_ml, hipStream_t st) {
   const int units = g.n_qb * g.group;
   const int f = BK32 ? 2 : 1;          // mask bits per 64 keys
   const dim3 grid((unsigned)(units * g.n_kvh));
@@ -559,10 +661,14 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
   if (!row_counts || g.words <= kWindowMinWords * f) {
-    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, o, o32,
-                                                             lse, all, nullptr, nullptr);
+    // (one sweep per row: every row reads K', V' of the whole sequence, and moving rows to another XCD costs
+    // more L2 misses than the balance gains: 3.1 against 2.7 ms at 32K)
+    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, nullptr,
+                                                             o, o32, lse, all, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
   }
+  balance_kernel<<<dim3(1), dim3(1024), 0, st>>>(g, row_counts, order, kLongRow * f, assign);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   // Long rows carry most of the work and keep scattered blocks over the whole sequence: swept
   // independently they miss L2 on most loads.  They are processed one window of 8K tokens (4 MB of K', V'
   // per KV head: the size of an XCD's L2) at a time, all rows together, so that the window is served by
@@ -572,12 +678,13 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // then costs more than the window saves).  Up to 32K tokens one sweep is faster.
   // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
   for (int w = 0; w < g.words; w += kWindowWords * f) {
-    const RowFilter lng = {row_counts, kLongRow * f + 1, 0x7FFFFFFF, w, kWindowWords * f};
-    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, o, o32, lse, lng, st_o, st_ml);
+    const RowFilter lng = {nullptr, 0, 0, w, kWindowWords * f};      // the table holds the long rows only
+    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, nullptr, assign, o, o32, lse, lng, st_o,
+                                                             st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
   const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow * f, -1, 0};
-  attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, o, o32, lse, shrt, nullptr,
+  attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, nullptr, o, o32, lse, shrt, nullptr,
                                                            nullptr);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
@@ -592,11 +699,13 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
   u32x4* kp = (u32x4*)ws;
   u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
-  // workspace: K' | V' | parked O^T state (32 KB per row block) | parked max / sum (1 KB) | unit order (i32)
+  // workspace: K' | V' | parked O^T state (32 KB per row block) | parked max / sum (1 KB) | unit order (i32) |
+  // balanced issue table (i32)
   const size_t n_units = (size_t)g.n_qh * g.n_qb;
   f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
   float* st_ml = (float*)(st_o + n_units * 2048);
   int32_t* order = (int32_t*)(st_ml + n_units * 256);
+  int32_t* assign = order + n_units;
   rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
                                                                                     (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
@@ -604,7 +713,7 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   Qk8 q8o = {nullptr, nullptr, nullptr, nullptr};
   if (qk8) {
     // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
-    const uintptr_t end = (uintptr_t)(order + n_units);
+    const uintptr_t end = (uintptr_t)(assign + n_units);
     const Int8Operands w = carve_int8_operands(p, (void*)((end + 63) & ~(uintptr_t)63));
     const int rc = launch_int8_operands(p, q, k, w, true, st);
     if (rc != SALE_OK) return rc;
@@ -614,23 +723,23 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   const bf16x8 *kpp = (const bf16x8*)kp, *vpp = (const bf16x8*)vp;
   if (mask) {
     if (g.bk == 32)
-      return qk8 ? launch_sparse_rows<true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse, st_o,
-                                                  st_ml, st)
-                 : launch_sparse_rows<true, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse,
-                                                   st_o, st_ml, st);
-    return qk8 ? launch_sparse_rows<false, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse, st_o,
-                                                 st_ml, st)
-               : launch_sparse_rows<false, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, (uint16_t*)o, o32, lse,
-                                                  st_o, st_ml, st);
+      return qk8 ? launch_sparse_rows<true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
+                                                  st_o, st_ml, st)
+                 : launch_sparse_rows<true, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
+                                                   lse, st_o, st_ml, st);
+    return qk8 ? launch_sparse_rows<false, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
+                                                 st_o, st_ml, st)
+               : launch_sparse_rows<false, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
+                                                  lse, st_o, st_ml, st);
   }
   const int units = g.n_qb * g.group;
   const RowFilter all = {nullptr, 0, 0, -1, 0};
   const dim3 grid((unsigned)(((units + 3) / 4) * g.n_kvh));
   if (qk8)
-    attn_rows_kernel<4, false, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, (uint16_t*)o, o32, lse,
-                                                                all, nullptr, nullptr);
+    attn_rows_kernel<4, false, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o, o32,
+                                                                lse, all, nullptr, nullptr);
   else
-    attn_rows_kernel<4, false, false><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, (uint16_t*)o, o32,
+    attn_rows_kernel<4, false, false><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o, o32,
                                                                  lse, all, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
