@@ -31,12 +31,17 @@ def _sample_units(w, n_q, k, seed):
 # A mid-size case just above the length from which long rows are swept window by window with parked
 # accumulators (9 mask words, ragged last window), with a low threshold so that many rows are long.
 LONG_ROWS_16K = inputs.Workload("gqa2-36k-long-rows", 36864, 4, 2, seed=0x5A1E0010, tau=0.0005)
+# The same with a single KV head (one lane: nothing to balance over the XCDs) and with three (an odd number of lanes).
+LONG_ROWS_1KV = inputs.Workload("gqa4-1kv-33k-long-rows", 33792, 4, 1, seed=0x5A1E0011, tau=0.0005)
+LONG_ROWS_3KV = inputs.Workload("gqa2-3kv-33k-long-rows", 33792, 6, 3, seed=0x5A1E0012, tau=0.001)
+EXTRA = {w.name: w for w in (LONG_ROWS_16K, LONG_ROWS_1KV, LONG_ROWS_3KV)}
 
 
-@pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 24), ("llama31-8b-layer-32k", 14),
+@pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 24), ("gqa4-1kv-33k-long-rows", 10),
+                                          ("gqa2-3kv-33k-long-rows", 12), ("llama31-8b-layer-32k", 14),
                                           ("llama31-8b-layer-64k", 12), ("llama31-8b-layer-128k", 12)])
 def test_full_size_sampled_parity(sale, name, n_units):
-    w = LONG_ROWS_16K if name == LONG_ROWS_16K.name else inputs.WORKLOADS[name]
+    w = EXTRA[name] if name in EXTRA else inputs.WORKLOADS[name]
     print(f"\n[{name}] generating inputs", flush=True)
     q, k, v = inputs.make_inputs(w)
     p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
