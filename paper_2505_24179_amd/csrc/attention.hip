@@ -98,11 +98,16 @@ __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16
 // win_word >= 0: only the key blocks of that 64-block mask word; a row then resumes from the state
 // (fp32 O^T accumulators, running max and sum, exactly the register contents) that the launch of the
 // previous word parked in the workspace, and parks it again unless this word holds its diagonal block.
+// Workgroups from number tail_from on (tail_from >= 0) form the tail of a window launch: they take the
+// rows the windows leave out (count <= count_max), whole, rank tail_phase + k * tail_stride of each KV head's
+// sorted list, so that every window launch ends with its share of short rows and its last long rows do
+// not leave the chip idle.
 struct RowFilter {
   const int32_t* counts;
   int count_min, count_max;
   int win_word;    // first mask word of the window, or < 0
   int win_words;   // words per window
+  int tail_from, tail_stride, tail_phase;
 };
 
 // order: optional [kv head][rank] -> unit id within the KV head (block * group + head-in-group).
@@ -132,12 +137,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   const int c = lane & 31, h = lane >> 5;
   const int units = g.n_qb * g.group;
   Unit u;
+  const bool tail = WAVES == 1 && flt.tail_from >= 0 && (int)blockIdx.x >= flt.tail_from;
   {
-    u.kvh = blockIdx.x % g.n_kvh;
-    const int rank = (blockIdx.x / g.n_kvh) * WAVES + wave;
+    const int b = tail ? (int)blockIdx.x - flt.tail_from : (int)blockIdx.x;
+    u.kvh = b % g.n_kvh;
+    const int rank = tail ? (b / g.n_kvh) * flt.tail_stride + flt.tail_phase : (b / g.n_kvh) * WAVES + wave;
     u.valid = rank < units;
     int id = !u.valid ? 0 : (order ? order[(size_t)u.kvh * units + rank] : units - 1 - rank);
-    if (assign) {
+    if (assign && !tail) {
       // balanced issue: slot `rank` of lane blockIdx % n_kvh holds a unit of ANY KV head (or nothing)
       const int entry = u.valid ? assign[(size_t)u.kvh * units + rank] : -1;
       u.valid = entry >= 0;
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   }
   if (!u.valid) return;
   const size_t unit_flat = (size_t)u.qh * g.n_qb + u.i;
-  if (flt.counts) {
+  if (flt.counts && (tail || flt.tail_from < 0)) {
     const int cnt = flt.counts[unit_flat];
     if (cnt < flt.count_min || cnt > flt.count_max) return;
   }
@@ -158,10 +165,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
   const int j_last = BK32 ? 2 * u.i + 1 : u.i;      // last causally visible mask bit of the row
   const int last_word = j_last >> 6;
-  if (flt.win_word > last_word) return;
-  const int word_lo = flt.win_word >= 0 ? flt.win_word : 0;
-  const int word_hi = flt.win_word >= 0 ? min(flt.win_word + flt.win_words - 1, last_word) : last_word;
-  const bool resume = flt.win_word > 0, park = flt.win_word >= 0 && word_hi < last_word;
+  const int win_word = tail ? -1 : flt.win_word;
+  if (win_word > last_word) return;
+  const int word_lo = win_word >= 0 ? win_word : 0;
+  const int word_hi = win_word >= 0 ? min(win_word + flt.win_words - 1, last_word) : last_word;
+  const bool resume = win_word > 0, park = win_word >= 0 && word_hi < last_word;
   auto row_word = [&](int wc) -> uint64_t {
     const int lo = wc * 64;
     const uint64_t causal = j_last >= lo + 63 ? ~0ull : ((2ull << (j_last - lo)) - 1ull);
@@ -655,7 +663,7 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   const int units = g.n_qb * g.group;
   const int f = BK32 ? 2 : 1;          // mask bits per 64 keys
   const dim3 grid((unsigned)(units * g.n_kvh));
-  const RowFilter all = {nullptr, 0, 0, -1, 0};
+  const RowFilter all = {nullptr, 0, 0, -1, 0, -1, 0, 0};
   if (row_counts) {
     order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
@@ -677,16 +685,18 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // 16K tokens 121 GB / 37.5 ms; 8K tokens 57 GB / 37.4 ms; 4K tokens 50 GB / 39.1 ms (the parked state
   // then costs more than the window saves).  Up to 32K tokens one sweep is faster.
   // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
-  for (int w = 0; w < g.words; w += kWindowWords * f) {
-    const RowFilter lng = {nullptr, 0, 0, w, kWindowWords * f};      // the table holds the long rows only
-    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, nullptr, assign, o, o32, lse, lng, st_o,
-                                                             st_ml);
+  // They are dealt over the window launches: launch number n ends with ranks n, n + launches, ... of every
+  // KV head's sorted list (the tail of the grid), which fill the chip while its last long rows finish.
+  const int step = kWindowWords * f, launches = (g.words + step - 1) / step;
+  const int tail_wgs = ((units + launches - 1) / launches) * g.n_kvh;
+  for (int n = 0; n < launches; ++n) {
+    // (the table holds the long rows only; the count filter applies to the tail)
+    const RowFilter flt = {row_counts, -0x7FFFFFFF, kLongRow * f, n * step, step, (int)grid.x, launches, n};
+    attn_rows_kernel<1, BK32, QK8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, assign,
+                                                                                          o, o32, lse, flt, st_o, st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
-  const RowFilter shrt = {row_counts, -0x7FFFFFFF, kLongRow * f, -1, 0};
-  attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, nullptr, o, o32, lse, shrt, nullptr,
-                                                           nullptr);
-  return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
+  return SALE_OK;
 }
 
 }  // namespace
@@ -733,7 +743,7 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
                                                   lse, st_o, st_ml, st);
   }
   const int units = g.n_qb * g.group;
-  const RowFilter all = {nullptr, 0, 0, -1, 0};
+  const RowFilter all = {nullptr, 0, 0, -1, 0, -1, 0, 0};
   const dim3 grid((unsigned)(((units + 3) / 4) * g.n_kvh));
   if (qk8)
     attn_rows_kernel<4, false, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o, o32,
