@@ -53,11 +53,11 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
     case SALE_WS_SPARSE_ATTN:
     case SALE_WS_DENSE_ATTN:
       // K and V copied once into MFMA fragment order, parked row state (fp32 O^T accumulators and
-      // max / sum per lane: 33 KB per 64-row block), the order in which rows are issued and the table that
-      // balances them over the XCDs
+      // max / sum per lane: 33 KB per 64-row block), the order in which rows are issued and the tables (one
+      // per window launch, at most 32) that balance them over the XCDs
       // (+ the 8-bit operand copies of the quantized Computation-Pass)
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
-             (rows / kBlockQ) * (2 * sizeof(int32_t) + 2048 * 16 + 256 * 4) +
+             (rows / kBlockQ) * ((1 + kMaskWordsMax / 2) * sizeof(int32_t) + 2048 * 16 + 256 * 4) + (128u << 10) + 16 +
              ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0);
     case SALE_WS_CALIBRATE:
       return calibrate_workspace_bytes(p);

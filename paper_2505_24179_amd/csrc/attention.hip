@@ -169,12 +169,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   if (win_word > last_word) return;
   const int word_lo = win_word >= 0 ? win_word : 0;
   const int word_hi = win_word >= 0 ? min(win_word + flt.win_words - 1, last_word) : last_word;
-  const bool resume = win_word > 0, park = win_word >= 0 && word_hi < last_word;
+  const bool park = win_word >= 0 && word_hi < last_word;
   auto row_word = [&](int wc) -> uint64_t {
     const int lo = wc * 64;
     const uint64_t causal = j_last >= lo + 63 ? ~0ull : ((2ull << (j_last - lo)) - 1ull);
     return mrow ? (mrow[wc] & causal) : causal;
   };
+  // A row takes part only in the windows where it keeps a block (and in its last one): it resumes iff an
+  // earlier window held one of its blocks.
+  bool resume = false;
+  if (win_word > 0) {
+    const uint64_t nonzero = __builtin_amdgcn_ballot_w64(lane < word_lo && row_word(lane) != 0ull);
+    resume = nonzero != 0ull;
+  }
 
   // ---- operands -----------------------------------------------------------------------
   // Q fragments (B operand of S^T = K Q^T), resident for the whole row.
@@ -559,83 +566,162 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
 // Workgroups go to the XCDs round-robin, so "lane" blockIdx % n_kvh of a launch always runs on the same XCDs.
 // With lane = KV head an XCD's L2 serves one head's K', V', but the heads of a layer keep very different
 // numbers of blocks (1.6x between the lightest and the heaviest at 128K here) and the light XCDs would idle.
-// This table moves a representative sample (every so-many-th of the sorted list) of the units of every
-// over-loaded head to the lanes of the under-loaded ones, in proportion to what they lack:
-// assign[lane][slot] = kvh * units + unit id, or -1.  Units with count <= min_count do not take part.
-// One workgroup.  Falls back to lane = KV head when there are too many lanes or a lane would overflow.
+// For every window launch (one workgroup of this kernel each) a table moves a representative sample (every
+// so-many-th of the sorted list) of the units of every over-loaded head to the lanes of the under-loaded
+// ones, in proportion to the work they lack in THAT window:
+//   assign[window][lane][slot] = kvh * units + unit id, or -1.
+// A unit takes part in a window if its row is long (count > min_count) and keeps a block there, or if the
+// window holds its diagonal block (where the row is finished whatever it keeps).
+// Falls back to lane = KV head when there are too many lanes or a lane would overflow.
 constexpr int kMaxLanes = 256;
-__global__ __launch_bounds__(1024) void balance_kernel(Geo g, const int32_t* __restrict__ row_counts,
-                                                       const int32_t* __restrict__ order, int min_count,
-                                                       int32_t* __restrict__ assign) {
-  __shared__ int n_in[kMaxLanes], n_shed[kMaxLanes], shed_off[kMaxLanes], recv_lo[kMaxLanes + 1];
-  __shared__ unsigned long long work[kMaxLanes];
-  const int units = g.n_qb * g.group, lanes = g.n_kvh;
-  const int total = lanes * units;
-  auto count_of = [&](int h, int id) {
-    return row_counts[(size_t)(h * g.group + id % g.group) * g.n_qb + id / g.group];
-  };
-  for (int e = threadIdx.x; e < total; e += blockDim.x) assign[e] = -1;
-  for (int h = threadIdx.x; h < min(lanes, kMaxLanes); h += blockDim.x) { n_in[h] = 0; work[h] = 0; }
-  __syncthreads();
-  const bool balance = lanes <= kMaxLanes && lanes > 1;
-  if (balance) {      // every thread sums a contiguous piece (mostly one head) and adds it once per head
-    const int per = (total + (int)blockDim.x - 1) / (int)blockDim.x;
-    const int e0 = threadIdx.x * per, e1 = min(e0 + per, total);
-    int h_run = -1, n_run = 0;
-    unsigned long long w_run = 0;
-    for (int e = e0; e < e1; ++e) {
-      const int h = e / units, c = count_of(h, e % units);
-      if (h != h_run) {
-        if (n_run) { atomicAdd(&n_in[h_run], n_run); atomicAdd(&work[h_run], w_run); }
-        h_run = h; n_run = 0; w_run = 0;
-      }
-      if (c > min_count) { ++n_run; w_run += (unsigned long long)c; }
+struct LaneLoad { unsigned long long work; int n_in; int pad; };      // per (window, KV head)
+constexpr size_t kLaneLoadBytes = (size_t)(kMaskWordsMax / 2) * kMaxLanes * sizeof(LaneLoad);      // 128 KB
+
+// Shared by the two kernels below: the units of ONE head in ONE window, 1024 threads, thread t looks at the
+// ranks t * per .. of the head's sorted list.
+struct WindowScan {
+  const Geo& g;
+  const uint64_t* mask;
+  const int32_t* row_counts;
+  const int32_t* order;
+  int min_count, w0, w1, bits_per_q, units;
+  // blocks the unit at rank r of head h keeps in this window (-1: it does not take part)
+  __device__ int in_window(int h, int r, int& id) const {
+    id = order[(size_t)h * units + r];
+    const int i = id / g.group, qh = h * g.group + id % g.group;
+    if (row_counts[(size_t)qh * g.n_qb + i] <= min_count) return -1;
+    const int j_last = (i + 1) * bits_per_q - 1, last_word = j_last >> 6;
+    if (w0 > last_word) return -1;
+    const uint64_t* mrow = mask + ((size_t)qh * g.n_qb + i) * g.words;
+    int c = 0;
+    for (int wc = w0; wc < min(w1, last_word + 1); ++wc) {
+      const int lo = wc * 64;
+      const uint64_t causal = j_last >= lo + 63 ? ~0ull : ((2ull << (j_last - lo)) - 1ull);
+      c += __popcll(mrow[wc] & causal);
     }
-    if (n_run) { atomicAdd(&n_in[h_run], n_run); atomicAdd(&work[h_run], w_run); }
+    return (c > 0 || w1 > last_word) ? c : -1;
+  }
+};
+
+// exclusive prefix over a 1024-thread workgroup of a per-thread count; total in `sum`
+__device__ __forceinline__ int block_scan_1024(int v, int* wave_sum, int& sum) {
+  const int lane_id = threadIdx.x & 63, wave_id = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(inc, off, 64);
+    if (lane_id >= off) inc += o;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (lane_id == 63) wave_sum[wave_id] = inc;
+  __syncthreads();
+  int base = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int x = wave_sum[w];
+    if (w < wave_id) base += x;
+    all += x;
+  }
+  sum = all;
+  return base + inc - v;
+}
+
+// Workgroup (window, head): number of participating units and their work in the window; clears the head's
+// own lane of the window's table.
+__global__ __launch_bounds__(1024) void window_load_kernel(Geo g, const uint64_t* __restrict__ mask,
+                                                           const int32_t* __restrict__ row_counts,
+                                                           const int32_t* __restrict__ order, int min_count, int win_words,
+                                                           int bits_per_q, LaneLoad* __restrict__ load,
+                                                           int32_t* __restrict__ assign_all) {
+  __shared__ int wave_sum[16];
+  __shared__ unsigned long long work;
+  const int units = g.n_qb * g.group, lanes = g.n_kvh;
+  const int win = blockIdx.x / lanes, h = blockIdx.x % lanes;
+  const int tid = threadIdx.x, per = (units + 1023) / 1024;
+  const WindowScan ws = {g, mask, row_counts, order, min_count, win * win_words, (win + 1) * win_words, bits_per_q, units};
+  int32_t* mine = assign_all + ((size_t)win * lanes + h) * units;
+  for (int e = tid; e < units; e += 1024) mine[e] = -1;
+  if (tid == 0) work = 0;
+  int n_mine = 0;
+  unsigned long long w_mine = 0;
+  for (int r = tid * per; r < min((tid + 1) * per, units); ++r) {
+    int id;
+    const int c = ws.in_window(h, r, id);
+    if (c >= 0) { ++n_mine; w_mine += (unsigned long long)c; }
+  }
+  int n_tot;
+  block_scan_1024(n_mine, wave_sum, n_tot);      // (its barriers also publish work = 0)
+  if (w_mine) atomicAdd(&work, w_mine);
+  __syncthreads();
+  if (tid == 0 && h < kMaxLanes) { load[win * kMaxLanes + h].work = work; load[win * kMaxLanes + h].n_in = n_tot; }
+}
+
+// Workgroup (window, head): places the head's participating units in the window's table.
+__global__ __launch_bounds__(1024) void balance_kernel(Geo g, const uint64_t* __restrict__ mask,
+                                                       const int32_t* __restrict__ row_counts,
+                                                       const int32_t* __restrict__ order, int min_count, int win_words,
+                                                       int bits_per_q, const LaneLoad* __restrict__ load,
+                                                       int32_t* __restrict__ assign_all) {
+  __shared__ int n_shed_h, shed_off_h, n_in_h, recv_lo[kMaxLanes + 1];
+  __shared__ int wave_sum[16];
+  const int units = g.n_qb * g.group, lanes = g.n_kvh;
+  const int win = blockIdx.x / lanes, h = blockIdx.x % lanes;
+  const int tid = threadIdx.x, per = (units + 1023) / 1024;
+  const WindowScan ws = {g, mask, row_counts, order, min_count, win * win_words, (win + 1) * win_words, bits_per_q, units};
+  int32_t* assign = assign_all + (size_t)win * lanes * units;
+  const bool balance = lanes <= kMaxLanes && lanes > 1;
+  if (tid == 0) {
+    n_shed_h = 0; shed_off_h = 0; n_in_h = 1;
+    for (int l = 0; l <= min(lanes, kMaxLanes); ++l) recv_lo[l] = 0;
     if (balance) {
+      const LaneLoad* ld = load + win * kMaxLanes;
       unsigned long long sum = 0;
-      for (int h = 0; h < lanes; ++h) sum += work[h];
+      for (int l = 0; l < lanes; ++l) sum += ld[l].work;
       const double target = (double)sum / lanes;
       double lack_total = 0.0;
-      int shed_total = 0;
-      for (int h = 0; h < lanes; ++h) {
-        const double w = (double)work[h];
-        n_shed[h] = w > target ? (int)((double)n_in[h] * (w - target) / w) : 0;
-        shed_off[h] = shed_total;
-        shed_total += n_shed[h];
+      int shed_total = 0, my_shed = 0, my_off = 0;
+      for (int l = 0; l < lanes; ++l) {
+        const double w = (double)ld[l].work;
+        const int ns = w > target ? (int)((double)ld[l].n_in * (w - target) / w) : 0;
+        if (l == h) { my_shed = ns; my_off = shed_total; }
+        shed_total += ns;
         if (w < target) lack_total += target - w;
       }
-      // the shed units, numbered shed_off[h] + k, go to the lanes that lack work, in proportion
+      // the shed units, numbered (offset of their head) + k, go to the lanes that lack work, in proportion
       double lack_run = 0.0;
-      bool ok = true;
-      for (int l = 0; l < lanes; ++l) {
-        recv_lo[l] = lack_total > 0.0 ? (int)((double)shed_total * (lack_run / lack_total)) : 0;
-        const double w = (double)work[l];
+      bool ok = lack_total > 0.0;
+      for (int l = 0; l < lanes && ok; ++l) {
+        recv_lo[l] = (int)((double)shed_total * (lack_run / lack_total));
+        const double w = (double)ld[l].work;
         if (w < target) lack_run += target - w;
       }
       recv_lo[lanes] = shed_total;
-      for (int l = 0; l < lanes; ++l) ok = ok && (n_in[l] - n_shed[l] + recv_lo[l + 1] - recv_lo[l] <= units);
-      if (!ok || lack_total <= 0.0) {
-        for (int h = 0; h < lanes; ++h) { n_shed[h] = 0; shed_off[h] = 0; }
-        for (int l = 0; l <= lanes; ++l) recv_lo[l] = 0;
+      for (int l = 0; l < lanes && ok; ++l) {
+        const double w = (double)ld[l].work;
+        const int ns = w > target ? (int)((double)ld[l].n_in * (w - target) / w) : 0;
+        ok = ld[l].n_in - ns + recv_lo[l + 1] - recv_lo[l] <= units;
       }
+      if (ok) { n_shed_h = my_shed; shed_off_h = my_off; n_in_h = max(ld[h].n_in, 1); }
+      else for (int l = 0; l <= lanes; ++l) recv_lo[l] = 0;
     }
   }
-  __syncthreads();
-  // order[h][r], r < n_in[h], are the participating units of head h, longest first
-  for (int e = threadIdx.x; e < total; e += blockDim.x) {
-    const int h = e / units, r = e % units;
-    const int id = order[(size_t)h * units + r];
-    if (count_of(h, id) <= min_count) continue;
+  int n_mine = 0;
+  for (int rr = tid * per; rr < min((tid + 1) * per, units); ++rr) {
+    int id;
+    if (ws.in_window(h, rr, id) >= 0) ++n_mine;
+  }
+  int n_tot;
+  int r = block_scan_1024(n_mine, wave_sum, n_tot);      // (its barriers also publish thread 0's parameters)
+  // r counts the participating units of the head in sorted order (longest rows first)
+  for (int rr = tid * per; rr < min((tid + 1) * per, units); ++rr) {
+    int id;
+    if (ws.in_window(h, rr, id) < 0) continue;
     int lane = h, pos = r;
     if (balance) {
-      const long long ns = n_shed[h], n = n_in[h];
+      const long long ns = n_shed_h, n = n_in_h;
       const int before = (int)((long long)r * ns / n), upto = (int)((long long)(r + 1) * ns / n);
       if (upto > before) {                      // this unit is shed: global shed number p
-        const int p = shed_off[h] + before;
+        const int p = shed_off_h + before;
         int l = 0;
         while (l + 1 < lanes && recv_lo[l + 1] <= p) ++l;
         lane = l;
@@ -647,6 +733,7 @@ __global__ __launch_bounds__(1024) void balance_kernel(Geo g, const int32_t* __r
       }
     }
     assign[(size_t)lane * units + pos] = h * units + id;
+    ++r;
   }
 }
 
@@ -675,8 +762,7 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
                                                              o, o32, lse, all, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
   }
-  balance_kernel<<<dim3(1), dim3(1024), 0, st>>>(g, row_counts, order, kLongRow * f, assign);
-  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+
   // Long rows carry most of the work and keep scattered blocks over the whole sequence: swept
   // independently they miss L2 on most loads.  They are processed one window of 8K tokens (4 MB of K', V'
   // per KV head: the size of an XCD's L2) at a time, all rows together, so that the window is served by
@@ -689,11 +775,18 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // KV head's sorted list (the tail of the grid), which fill the chip while its last long rows finish.
   const int step = kWindowWords * f, launches = (g.words + step - 1) / step;
   const int tail_wgs = ((units + launches - 1) / launches) * g.n_kvh;
+  LaneLoad* load = (LaneLoad*)(((uintptr_t)(assign + (size_t)(kMaskWordsMax / 2) * grid.x) + 15) & ~(uintptr_t)15);
+  window_load_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, row_counts, order, kLongRow * f,
+                                                                                 step, f, load, assign);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  balance_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, row_counts, order, kLongRow * f, step,
+                                                                             f, load, assign);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   for (int n = 0; n < launches; ++n) {
     // (the table holds the long rows only; the count filter applies to the tail)
     const RowFilter flt = {row_counts, -0x7FFFFFFF, kLongRow * f, n * step, step, (int)grid.x, launches, n};
-    attn_rows_kernel<1, BK32, QK8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, order, assign,
-                                                                                          o, o32, lse, flt, st_o, st_ml);
+    attn_rows_kernel<1, BK32, QK8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(
+        g, q, kp, vp, q8o, mask, order, assign + (size_t)n * grid.x, o, o32, lse, flt, st_o, st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
   return SALE_OK;
@@ -710,7 +803,7 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   u32x4* kp = (u32x4*)ws;
   u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
   // workspace: K' | V' | parked O^T state (32 KB per row block) | parked max / sum (1 KB) | unit order (i32) |
-  // balanced issue table (i32)
+  // balanced issue tables (i32, room for 32 window launches)
   const size_t n_units = (size_t)g.n_qh * g.n_qb;
   f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
   float* st_ml = (float*)(st_o + n_units * 2048);
@@ -723,7 +816,7 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   Qk8 q8o = {nullptr, nullptr, nullptr, nullptr};
   if (qk8) {
     // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
-    const uintptr_t end = (uintptr_t)(assign + n_units);
+    const uintptr_t end = (uintptr_t)(assign + n_units * (kMaskWordsMax / 2)) + 16 + kLaneLoadBytes;
     const Int8Operands w = carve_int8_operands(p, (void*)((end + 63) & ~(uintptr_t)63));
     const int rc = launch_int8_operands(p, q, k, w, true, st);
     if (rc != SALE_OK) return rc;
