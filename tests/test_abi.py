@@ -42,7 +42,7 @@ def test_status_strings(sale):
 def test_workspace_sizes(sale):
     p = sale.Params(1, 32, 8, 131072)
     assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4 + (32 + 8) * 131072 * 96
-    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 2 * 8 * 131072 * 128 * 2 + 32 * 2048 * (4 + 32768 + 1024)
+    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 2 * 8 * 131072 * 128 * 2 + 32 * 2048 * (33 * 4 + 32768 + 1024) + (128 << 10) + 16
     assert sale.workspace_bytes(p, sale.WS_DENSE_ATTN) == sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)
     assert sale.workspace_bytes(sale.Params(1, 32, 8, 100), sale.WS_SELECT) == 0   # invalid geometry
 
