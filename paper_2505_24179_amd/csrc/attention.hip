@@ -739,7 +739,7 @@ __global__ __launch_bounds__(1024) void balance_kernel(Geo g, const uint64_t* __
 
 constexpr int kLongRow = 192;        // rows keeping more than this (12K tokens) are swept window by window
 constexpr int kWindowWords = 2;      // window width in mask words of 64 x 64 keys: 8K tokens, 4 MB of K', V' per KV head
-constexpr int kWindowMinWords = 8;   // sequences of up to 32K tokens use one sweep per row
+constexpr int kWindowMinWords = 4;   // sequences of up to 16K tokens use one sweep per row
 
 namespace {
 
@@ -769,7 +769,8 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // the L2 of the XCD that owns the KV head; their accumulators wait in the workspace in between.
   // Measured at 128K tokens (L2 fills / time of the call): one sweep per row 218 GB / 50.7 ms; windows of
   // 16K tokens 121 GB / 37.5 ms; 8K tokens 57 GB / 37.4 ms; 4K tokens 50 GB / 39.1 ms (the parked state
-  // then costs more than the window saves).  Up to 32K tokens one sweep is faster.
+  // then costs more than the window saves).  At 32K tokens windows (with the balancing below) and one sweep
+  // per row are within 2 % of each other; shorter sequences use one sweep.
   // Short rows keep little besides the sink, the local band and the heavy columns everyone shares.
   // They are dealt over the window launches: launch number n ends with ranks n, n + launches, ... of every
   // KV head's sorted list (the tail of the grid), which fill the chip while its last long rows finish.
