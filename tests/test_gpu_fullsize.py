@@ -211,3 +211,58 @@ def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
         worst_s, worst_d = max(worst_s, ms), max(worst_d, md)
         print(f"[{name} int8] unit (h={h}, i={i}) kept {int(got_row.sum())}/{i + 1} ok", flush=True)
     print(f"[{name} int8] max abs err sparse {worst_s:.3g} dense {worst_d:.3g}")
+
+
+def _popcount64(x: torch.Tensor) -> torch.Tensor:
+    """Population count of int64 words (bit patterns), on the GPU."""
+    c = torch.zeros_like(x)
+    for s in range(0, 64, 8):
+        b = (x >> s) & 0xFF
+        b = (b & 0x55) + ((b >> 1) & 0x55)
+        b = (b & 0x33) + ((b >> 2) & 0x33)
+        c += (b & 0x0F) + (b >> 4)
+    return c
+
+
+@pytest.mark.parametrize("bk", [64, 32])
+def test_full_size_properties_over_every_row_128k(sale, bk):
+    """What must hold for EVERY row at the benchmark's size (the sampled test checks values on a few):
+    counts = popcount; nothing above the causal boundary; sink and local blocks kept; masks nested in tau;
+    tau -> 0 keeps every causal block and then sparse == dense bit for bit; the kept probability mass
+    exp(lse_sparse - lse_dense) lies in (0, 1]."""
+    w = inputs.WORKLOADS["llama31-8b-layer-128k"]
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=bk)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    f = 64 // bk
+    i = torch.arange(p.n_q, device=dev)
+    j = torch.arange(p.words * 64, device=dev)
+    causal = (j[None, :] <= ((i + 1) * f - 1)[:, None]).view(p.n_q, p.words, 64)
+    weights = torch.tensor([1 << b for b in range(63)] + [-(1 << 63)], dtype=torch.int64, device=dev)
+    causal_words = (causal.long() * weights).sum(-1)                                 # [n_q, W] bit patterns
+    local = ((j[None, :] <= ((i + 1) * f - 1)[:, None]) & (j[None, :] > ((i + 1) * f - 1 - 4)[:, None])) | (j[None, :] == 0)
+    local_words = (local.view(p.n_q, p.words, 64).long() * weights).sum(-1)
+    masks = {}
+    for tau in (0.008, 0.004, 0.002, 1e-30):
+        t = torch.tensor([tau], dtype=torch.float32, device=dev)
+        mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, t)
+        assert torch.equal(_popcount64(mask[0]).sum(-1).int(), counts[0]), tau
+        assert not torch.any(mask[0] & ~causal_words[None]), tau
+        assert torch.equal(mask[0] & local_words[None], local_words[None].expand_as(mask[0])), tau
+        masks[tau] = (mask, counts)
+    for hi, lo in ((0.008, 0.004), (0.004, 0.002), (0.002, 1e-30)):
+        assert not torch.any(masks[hi][0] & ~masks[lo][0])                           # nested in tau
+    assert int(masks[0.008][1].sum()) < int(masks[0.004][1].sum()) < int(masks[0.002][1].sum())
+    assert torch.equal(masks[1e-30][0][0], causal_words[None].expand_as(masks[1e-30][0][0]))
+    ws = torch.empty(sale.workspace_bytes(p, sale.WS_SPARSE_ATTN), dtype=torch.uint8, device=dev)
+    o_all, lse_all = sale.sparse_attn(p, qd, kd, vd, *masks[1e-30], want_lse=True, ws=ws)
+    o_all = o_all.clone()
+    o_dense, lse_dense = sale.dense_attn(p, qd, kd, vd, want_lse=True, ws=ws)
+    assert torch.equal(o_all, o_dense) and torch.equal(lse_all, lse_dense)
+    o_sp, lse_sp = sale.sparse_attn(p, qd, kd, vd, *masks[0.004], want_lse=True, ws=ws)
+    assert torch.isfinite(o_sp.float()).all() and torch.isfinite(lse_sp).all()
+    mass = torch.exp(lse_sp - lse_dense)
+    assert float(mass.max()) <= 1.0 + 2 * LSE_ATOL and float(mass.min()) > 0.0
+    print(f"[128k 64x{bk}] kept probability mass: min {float(mass.min()):.3f} mean {float(mass.mean()):.4f}")
