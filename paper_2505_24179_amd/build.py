@@ -45,7 +45,25 @@ def build(extra_flags=(), verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print("built", LIB)
+    _build_c_abi_check(verbose)
     return LIB
+
+
+def _build_c_abi_check(verbose: bool) -> None:
+    """tests/c_abi/abi_check: a plain-C (gcc) user of include/sale.h, run by the GPU tests."""
+    src = os.path.join(ROOT, "tests", "c_abi", "abi_check.c")
+    if not os.path.exists(src):
+        return
+    exe = os.path.join(ROOT, "tests", "c_abi", "abi_check")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(ROOT, "include"), src, "-o", exe, "-L", PKG, "-lsale", "-L", os.path.join(rocm, "lib"),
+           "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN/../../paper_2505_24179_amd", f"-Wl,-rpath,{os.path.join(rocm, 'lib')}"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("gcc failed for abi_check.c:\n" + r.stderr)
+    if verbose:
+        print("built", exe)
 
 
 if __name__ == "__main__":
