@@ -24,12 +24,17 @@
 //   (exactly) whenever no row maximum grew; O accumulates in fp32.
 // * Scheduling.  Dense: a workgroup is the 4 units of one GQA group at the same
 //   query block (they read the same blocks in step, so three of four loads hit
-//   L1), longest rows first.  Sparse: row lengths are heavy-tailed (a query
-//   block with one weak row keeps everything), so every unit is its own
-//   64-thread workgroup and the units of each KV head are issued in order of
-//   decreasing kept-block count (a counting sort of row_counts).  In both,
-//   workgroups go round-robin over KV heads (blockIdx % n_kv_heads: one KV
-//   head per XCD / L2 when there are 8).
+//   L1), longest rows first, workgroups round-robin over KV heads (blockIdx %
+//   n_kv_heads: one KV head per XCD / L2 when there are 8).
+//   Sparse: row lengths are heavy-tailed (a query block with one weak row keeps
+//   everything) and differ between heads, so every unit is its own 64-thread
+//   workgroup.  Short sequences: one sweep per row, rows issued by decreasing
+//   kept-block count (a counting sort of row_counts).  Longer ones: the long
+//   rows are swept window by window (a window of K', V' fits an XCD's L2) with
+//   their accumulators parked in the workspace in between, every window launch
+//   is balanced over the XCDs by a table that moves rows of over-loaded heads to
+//   the lanes of under-loaded ones, and the short rows ride at the tail of the
+//   window launches (details at launch_sparse_rows and balance_kernel).
 #include <type_traits>
 
 #include "sale_common.h"
