@@ -266,3 +266,34 @@ def test_full_size_properties_over_every_row_128k(sale, bk):
     mass = torch.exp(lse_sp - lse_dense)
     assert float(mass.max()) <= 1.0 + 2 * LSE_ATOL and float(mass.min()) > 0.0
     print(f"[128k 64x{bk}] kept probability mass: min {float(mass.min()):.3f} mean {float(mass.mean()):.4f}")
+
+
+def test_many_kv_heads_beyond_the_balancing_table(sale):
+    """264 (batch x KV head) lanes: more than the balancing tables hold, so the windowed sweep falls back to
+    lane = KV head.  The result must agree with the one-sweep-per-row path (no counts given) up to the rounding
+    of a different summation order, and a few units are checked against the oracle."""
+    w = inputs.Workload("mha-17k", 17408, 1, 1, seed=0x5A1E0020, tau=0.002)
+    q, k, v = inputs.make_inputs(w)
+    B = 264
+    g = torch.Generator().manual_seed(5)
+    scale = 0.75 + 0.5 * torch.rand(B, 1, 1, 1, generator=g)              # the batch entries differ
+    qb = (q[None].float() * scale).bfloat16().cuda()
+    kb = k[None].expand(B, -1, -1, -1).contiguous().cuda()
+    vb = v[None].expand(B, -1, -1, -1).contiguous().cuda()
+    p = sale.Params(B, 1, 1, w.seq_len)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    q4, k4, qs, ks = sale.quantize_qk(p, qb, kb)
+    mask, counts, _, _ = sale.select(p, qb, kb, q4, k4, qs, ks, tau)
+    assert int((counts > 192).sum()) > 1000                               # many long rows: the windowed path runs
+    o_win, _ = sale.sparse_attn(p, qb, kb, vb, mask, counts)
+    o_one, _ = sale.sparse_attn(p, qb, kb, vb, mask, None)
+    torch.cuda.synchronize()
+    d = (o_win.float() - o_one.float()).abs()
+    assert float(d.max()) <= 2e-2 and float(d.mean()) <= 2e-4
+    geo = so.Geometry(w.seq_len, w.head_dim)
+    kf, vf = k[0].float().numpy(), v[0].float().numpy()
+    for b, i in ((0, geo.n_q - 1), (131, 200), (263, geo.n_q - 1), (263, 5)):
+        rs = slice(i * 64, (i + 1) * 64)
+        row = words_to_bool(mask[b, 0, i].cpu().numpy(), p.n_k)
+        ref, _ = so.attention_block(geo, i, qb[b, 0, rs].float().cpu().numpy(), kf, vf, row)
+        check_output(o_win[b, 0, rs].float().cpu().numpy(), ref, f"264 lanes b{b} i{i}")
