@@ -518,12 +518,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     sml[0] = m_run[0]; sml[64] = m_run[1]; sml[128] = l_run[0]; sml[192] = l_run[1];
     return;
   }
+  // Output.  A lane holds, per (nt, dt, q4), four consecutive channels of one query row: stored from there a
+  // store instruction touches 32 rows, 16 bytes each.  The bf16 tile goes through LDS instead (rows padded by
+  // four banks) and leaves as whole 256-byte rows, 4 rows per instruction.
+  constexpr int kRowPad = kHeadDim + 8;      // bf16 elements per LDS row
+  __shared__ __attribute__((aligned(16))) uint16_t o_lds[WAVES * 64 * kRowPad];
+  uint16_t* const tile = o_lds + wave * 64 * kRowPad;
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_run[nt] + swap_half(l_run[nt]);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     const size_t row = (size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c;
-    uint16_t* orow = o + row * kHeadDim + 4 * h;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -537,10 +542,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
           bf16x4 w;
 #pragma unroll
           for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[dt][nt][4 * q4 + e] * inv);
-          *(bf16x4*)(orow + 32 * dt + 8 * q4) = w;
+          *(bf16x4*)(tile + (32 * nt + c) * kRowPad + 4 * h + 32 * dt + 8 * q4) = w;
         }
       }
     if (lse && h == 0) lse[row] = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(l_tot) : -INFINITY;
+  }
+  if (!o32) {
+    // (each wave reads back only its own tile: no barrier, LDS operations of a wave complete in order)
+    uint16_t* const out = o + ((size_t)u.qh * g.seq + u.i * 64) * kHeadDim;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int r = 4 * it + (lane >> 4), ch = 8 * (lane & 15);
+      *(u32x4*)(out + r * kHeadDim + ch) = *(const u32x4*)(tile + r * kRowPad + ch);
+    }
   }
 }
 
