@@ -4,7 +4,8 @@
 // with.  Workgroups of 256 threads; the dynamic LDS request decides how many fit a CU, i.e. how many waves
 // share a SIMD (1, 2 or 4).  Every wave runs the same unrolled body on registers only.
 //   * 128 independent VALU instructions of one kind per iteration;
-//   * two v_mfma_f32_32x32x16_bf16 on two accumulators, each followed by n fp32 FMAs that depend on neither.
+//   * two v_mfma_f32_32x32x16_bf16 (or two FP6 v_mfma_scale_f32_32x32x64_f8f6f4) on two accumulators, each
+//     followed by n fp32 FMAs that depend on neither.
 // Prints SIMD cycles per instruction (all waves of the SIMD counted) at a nominal 2.4 GHz.
 //
 //   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops issue_cost.hip -o issue_cost
@@ -24,8 +25,9 @@
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 
-enum { kFma = 0, kExp2, kCvtPk, kDot2, kMax3, kSwap32, kMfma = 10 };      // kMfma + n: MFMA followed by n FMAs
+enum { kFma = 0, kExp2, kCvtPk, kDot2, kMax3, kSwap32, kMfma = 10, kMfma6 = 40 };      // kMfma(6) + n: MFMA followed by n FMAs
 
 template <int MODE>
 __global__ __launch_bounds__(256) void probe(float* out, int iters, float seed) {
@@ -38,7 +40,18 @@ __global__ __launch_bounds__(256) void probe(float* out, int iters, float seed) 
   for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(seed + i); b[i] = (__bf16)(seed * 0.5f + i); }
   bf16x2 ones;
   ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
+  i32x8 a6, b6;
+  for (int i = 0; i < 8; ++i) { a6[i] = i < 6 ? (int)threadIdx.x * 0x01010101 : 0; b6[i] = i < 6 ? 0x08080808 : 0; }
   for (int it = 0; it < iters; ++it) {
+    if (MODE >= kMfma6) {
+      acc0 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a6, b6, acc0, 2, 2, 0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < MODE - kMfma6; ++i) x[i] = __builtin_fmaf(x[i], 0.999f, 0.001f);
+      acc1 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a6, b6, acc1, 2, 2, 0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < MODE - kMfma6; ++i) x[i] = __builtin_fmaf(x[i], 0.998f, 0.002f);
+      continue;
+    }
     if (MODE >= kMfma) {
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc0, 0, 0, 0);
 #pragma unroll
@@ -101,6 +114,10 @@ int main() {
       return 1;
     if (run<kMfma>("mfma", 2, w) || run<kMfma + 2>("mfma + 2 fma", 2, w) || run<kMfma + 4>("mfma + 4 fma", 2, w) ||
         run<kMfma + 6>("mfma + 6 fma", 2, w) || run<kMfma + 8>("mfma + 8 fma", 2, w) || run<kMfma + 12>("mfma + 12 fma", 2, w))
+      return 1;
+    if (run<kMfma6>("fp6 mfma", 2, w) || run<kMfma6 + 2>("fp6 mfma + 2 fma", 2, w) || run<kMfma6 + 4>("fp6 mfma + 4 fma", 2, w) ||
+        run<kMfma6 + 6>("fp6 mfma + 6 fma", 2, w) || run<kMfma6 + 8>("fp6 mfma + 8 fma", 2, w) ||
+        run<kMfma6 + 12>("fp6 mfma + 12 fma", 2, w))
       return 1;
   }
   return 0;
