@@ -34,12 +34,15 @@ LONG_ROWS_16K = inputs.Workload("gqa2-36k-long-rows", 36864, 4, 2, seed=0x5A1E00
 # The same with a single KV head (one lane: nothing to balance over the XCDs) and with three (an odd number of lanes).
 LONG_ROWS_1KV = inputs.Workload("gqa4-1kv-33k-long-rows", 33792, 4, 1, seed=0x5A1E0011, tau=0.0005)
 LONG_ROWS_3KV = inputs.Workload("gqa2-3kv-33k-long-rows", 33792, 6, 3, seed=0x5A1E0012, tau=0.001)
-EXTRA = {w.name: w for w in (LONG_ROWS_16K, LONG_ROWS_1KV, LONG_ROWS_3KV)}
+# The longest sequence the path accepts with 64-key blocks: 4096 key blocks, all 64 mask words, 32 window launches.
+MAX_LENGTH_256K = inputs.Workload("gqa2-1kv-256k-max-length", 262144, 2, 1, seed=0x5A1E0013, tau=0.004)
+EXTRA = {w.name: w for w in (LONG_ROWS_16K, LONG_ROWS_1KV, LONG_ROWS_3KV, MAX_LENGTH_256K)}
 
 
 @pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 24), ("gqa4-1kv-33k-long-rows", 10),
                                           ("gqa2-3kv-33k-long-rows", 12), ("llama31-8b-layer-32k", 14),
-                                          ("llama31-8b-layer-64k", 12), ("llama31-8b-layer-128k", 12)])
+                                          ("llama31-8b-layer-64k", 12), ("llama31-8b-layer-128k", 12),
+                                          ("gqa2-1kv-256k-max-length", 6)])
 def test_full_size_sampled_parity(sale, name, n_units):
     w = EXTRA[name] if name in EXTRA else inputs.WORKLOADS[name]
     print(f"\n[{name}] generating inputs", flush=True)
