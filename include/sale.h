@@ -25,6 +25,13 @@
  *   sale_qk_int4_products; seq_len a multiple of 64 and at most 4096 key
  *   blocks; n_q_heads a multiple of n_kv_heads.  (sale_quantize_qk alone also
  *   accepts block_q = 32.)  Anything else returns SALE_ERR_UNSUPPORTED.
+ *   A sequence whose length is not a multiple of 64 is passed zero-padded to
+ *   the next multiple: attention is causal, so no valid query row ever sees a
+ *   padded key and the outputs of the valid rows are those of the unpadded
+ *   sequence under the returned mask; only the mask row of the last query
+ *   block is then chosen with its padded (all-zero) query rows taking part, and
+ *   the statistics of its valid rows see the padded keys of the diagonal block
+ *   unless SALE_FLAG_STATS_CAUSAL is set.
  *
  * Notation follows the paper: N = seq_len, d = head_dim, b_q / b_k block sizes,
  * N_q = N / b_q, N_k = N / b_k, M_bs the block-level sparse mask (Sec. 3.1),

@@ -21,7 +21,9 @@
 //   of the contraction index that the V copy applies as well), so P never
 //   leaves registers.
 // * Softmax in fp32 with exp2 and the scale folded in; the O rescale is skipped
-//   (exactly) whenever no row maximum grew; O accumulates in fp32.
+//   (exactly) whenever no row maximum grew; O accumulates in fp32.  The finished
+//   bf16 tile is transposed through LDS (each wave its own 17 KB, no barrier) so
+//   that it leaves as whole 256-byte rows.
 // * Scheduling.  Dense: a workgroup is the 4 units of one GQA group at the same
 //   query block (they read the same blocks in step, so three of four loads hit
 //   L1), longest rows first, workgroups round-robin over KV heads (blockIdx %

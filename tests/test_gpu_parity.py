@@ -253,6 +253,35 @@ def test_batch_two_equals_two_single_batches(sale):
         assert torch.equal(ob[0], o[b])
 
 
+def test_padded_tail_does_not_reach_valid_rows(sale):
+    """A sequence 48 tokens short of a multiple of 64, padded: attention is causal, so whatever the padding rows
+    of Q, K, V hold, the outputs of the valid rows are the same bit for bit (dense, and sparse under one mask), and
+    with causal statistics the mask rows of every query block but the last are the same too."""
+    w = CASES["gqa2-ragged"]
+    q, k, v = inputs.make_inputs(w)
+    n_valid = w.seq_len - 48
+    g = torch.Generator().manual_seed(7)
+    variants = []
+    for fill in ("zero", "noise"):
+        qq, kk, vv = q.clone(), k.clone(), v.clone()
+        for t in (qq, kk, vv):
+            t[:, n_valid:] = 0 if fill == "zero" else (torch.randn(t[:, n_valid:].shape, generator=g) * 3.0).to(t.dtype)
+        variants.append(_dev(qq, kk, vv))
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=sale.FLAG_STATS_CAUSAL)
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    outs = []
+    for qd, kd, vd in variants:
+        q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+        mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+        outs.append((mask, counts, sale.dense_attn(p, qd, kd, vd)[0]))
+    (m0, c0, d0), (m1, c1, d1) = outs
+    assert torch.equal(d0[:, :, :n_valid], d1[:, :, :n_valid])
+    assert torch.equal(m0[:, :, :-1], m1[:, :, :-1]) and torch.equal(c0[:, :, :-1], c1[:, :, :-1])
+    s0, _ = sale.sparse_attn(p, *variants[0], m0, c0)
+    s1, _ = sale.sparse_attn(p, *variants[1], m0, c0)
+    assert torch.equal(s0[:, :, :n_valid], s1[:, :, :n_valid])
+
+
 def test_repeat_runs_are_bit_identical(sale):
     """The path has no run-to-run freedom in its results (the row order of the sparse kernel is not
     deterministic, the rows are independent)."""
