@@ -74,25 +74,34 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
     // keys of this block that lie after a query row (only with SALE_FLAG_STATS_CAUSAL)
     const bool mask_diag = g.stats_causal && (j + 1) * g.bk - 1 > u.i * 64;
     const int ahead = j * g.bk - u.i * 64;      // first key of the block minus first query row
+    // (VALU-bound: per score one half of a v_max3, one FMA that folds 1 / sqrt(d), log2(e) and the maximum,
+    // one v_exp_f32 and one add; the causal select only where a block needs it)
+    if (mask_diag) {
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane))) acc[mt][nt][r] = -INFINITY;
+    }
+    const float kLog2e = 1.4426950408889634f;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      float s[MT * 16];
       float mx = -INFINITY;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float x = acc[mt][nt][r] * rsd;
-          x = (mask_diag & (ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane)))) ? -INFINITY : x;
-          s[mt * 16 + r] = x;
-          mx = fmaxf(mx, x);
-        }
-      const float m_new = fmaxf(m[nt], mx);
+        for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(mx, acc[mt][nt][r]), acc[mt][nt][r + 1]);
+      const float m_new = fmaxf(m[nt], mx * rsd);      // rsd > 0: the maximum of the products is the product of the maximum
       const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+      const float mb = m_safe * kLog2e;
       float sum = 0.0f;
 #pragma unroll
-      for (int e = 0; e < MT * 16; ++e) sum += __expf(s[e] - m_safe);
-      l[nt] = l[nt] * __expf(m[nt] - m_safe) + sum;
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][nt][r], rsd * kLog2e, -mb));
+      l[nt] = l[nt] * __builtin_amdgcn_exp2f(m[nt] * kLog2e - mb) + sum;
       m[nt] = m_new;
     }
   }
