@@ -21,7 +21,9 @@ against Eq. 4; structural invariants of the mask; attention with every block
 selected against brute-force causal softmax; the renormalisation identity for
 dropped blocks; the 8-bit Computation-Pass against the unquantized one (exact on
 the 8-bit grid, within the quantization-step bound elsewhere) and the softmax
-invariance of the K smoothing.  No function here is "parity unpinned".
+invariance of the K smoothing; the borderline band (is_borderline) against
+literal margins at |thr| <= 1, 10 and 100 and NaN margins.  No function here is
+"parity unpinned".
 """
 
 from __future__ import annotations

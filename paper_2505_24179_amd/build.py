@@ -46,28 +46,7 @@ def build(extra_flags=(), verbose: bool = True) -> str:
     if verbose:
         print("built", LIB)
     _build_c_abi_check(verbose)
-    _build_microbench(verbose)
     return LIB
-
-
-def _build_microbench(verbose: bool) -> None:
-    """microbench/*.hip: standalone probes (MFMA rates, issue costs); nothing loads them."""
-    folder = os.path.join(PKG, "microbench")
-    names = sorted(f[:-4] for f in os.listdir(folder) if f.endswith(".hip")) if os.path.isdir(folder) else []
-
-    def one(name: str) -> str:
-        exe = os.path.join(folder, name)
-        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               os.path.join(folder, name + ".hip"), "-o", exe]
-        r = subprocess.run(cmd, capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed for microbench/{name}.hip:\n{r.stderr}")
-        return exe
-
-    with ThreadPoolExecutor(max_workers=2) as ex:
-        for exe in ex.map(one, names):
-            if verbose:
-                print("built", exe)
 
 
 def _build_c_abi_check(verbose: bool) -> None:

@@ -291,3 +291,45 @@ def test_segment_rule_mask_is_the_plain_mask_with_the_remainder_kept():
             expect[i, j] = j in isl or bool((rel >= 0).any())
     np.testing.assert_array_equal(mask, expect)
     assert 0.1 < mask.sum() / so.dense_mask(geo).sum() < 0.95
+
+
+def test_is_borderline_band_is_1e5_relative_to_max_1_thr():
+    """The band that excuses GPU / oracle mask differences (spec: decisions within 1e-5 relative of the
+    threshold), fixed by literal cases: |margin| <= 1e-5 * max(1, |thr|), both signs, nothing else."""
+    # |thr| <= 1: the band is 1e-5 absolute, whatever thr is
+    for thr in (0.0, 0.5, -0.5, 1.0, -1.0):
+        for sign in (1.0, -1.0):
+            assert bool(so.is_borderline(np.float64(sign * 0.9e-5), np.float64(thr)))
+            assert not bool(so.is_borderline(np.float64(sign * 1.1e-5), np.float64(thr)))
+    # |thr| > 1: the band scales with |thr| (thr = +-10 -> 1e-4; thr = 100 -> 1e-3), not with thr's sign
+    for thr, band in ((10.0, 1e-4), (-10.0, 1e-4), (100.0, 1e-3)):
+        for sign in (1.0, -1.0):
+            assert bool(so.is_borderline(np.float64(sign * 0.9 * band), np.float64(thr)))
+            assert not bool(so.is_borderline(np.float64(sign * 1.1 * band), np.float64(thr)))
+    # exactly on the edge counts as borderline; zero margin always does
+    assert bool(so.is_borderline(np.float64(1e-5), np.float64(0.0)))
+    assert bool(so.is_borderline(np.float64(0.0), np.float64(123.0)))
+    # element-wise over arrays, thr broadcast per element
+    got = so.is_borderline(np.array([0.9e-5, 0.9e-4, 0.9e-4, -2.0]), np.array([0.0, 0.0, 10.0, 1e6]))
+    assert got.tolist() == [True, False, True, True]
+    # a NaN margin (no decision was taken for that block: sink / local / beyond the diagonal) is never borderline,
+    # neither raw nor after the substitution the parity helper applies (margin -> 1e30, thr -> 0)
+    assert not bool(so.is_borderline(np.float64("nan"), np.float64(0.0)))
+    assert not bool(so.is_borderline(np.float64("nan"), np.float64("nan")))
+    assert not bool(so.is_borderline(np.nan_to_num(np.float64("nan"), nan=1e30), np.nan_to_num(np.float64("nan"), nan=0.0)))
+    # the explicit rel argument replaces the 1e-5
+    assert bool(so.is_borderline(np.float64(0.9e-3), np.float64(0.0), 1e-3))
+    assert not bool(so.is_borderline(np.float64(1.1e-3), np.float64(0.0), 1e-3))
+
+
+def test_parity_helper_forgives_only_differences_inside_the_band():
+    """compare_mask_row (what every GPU mask test and the smoke check use) counts a differing decision as hard
+    unless its oracle margin is inside the band; blocks without a decision (NaN margin) are always hard."""
+    from parity_utils import compare_mask_row
+    ora = np.array([True, False, True, False, True])
+    gpu = np.array([False, True, True, True, False])              # differs at 0, 1, 3, 4
+    margin = np.array([0.5e-5, -3e-5, 0.0, np.nan, 2e-4])
+    thr = np.array([0.3, 0.3, 0.3, np.nan, 50.0])                 # band: 1e-5, 1e-5, -, never, 5e-4
+    hard, soft = compare_mask_row(gpu, ora, margin, thr)
+    assert (hard, soft) == (2, 2)
+    assert compare_mask_row(ora, ora, margin, thr) == (0, 0)
