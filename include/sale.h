@@ -165,7 +165,17 @@ int sale_select(const sale_params_t* p, const void* q, const void* k,
  *                   to order work
  *   o          out: bf16, layout of Q
  *   lse        out: optional (may be NULL) fp32 [batch][n_q_heads][N], natural-log
- *                   sum-exp of the kept logits of each row
+ *                   sum-exp of the kept logits S[r,c] = q_r . k_c / sqrt(d) of each row
+ *                   (Sec. 3.1).  Accuracy: within 5e-3 absolute of the exact value.
+ *                   The kernel sums the probabilities AFTER rounding them to bf16
+ *                   (the values it multiplies with V, so that numerator and
+ *                   denominator of O agree); bf16 keeps 8 significant bits, so
+ *                   the sum is within 2^-8 relative and its logarithm within
+ *                   3.9e-3.  A caller that merges partial results by lse
+ *                   inherits that 2^-8 relative weight error.  With
+ *                   SALE_FLAG_ATTN_INT8_QK the logits are the 8-bit estimates;
+ *                   the per-row shift q_r . k_mean / sqrt(d) that the K smoothing
+ *                   takes out is added back, so lse still refers to S above.
  *   ws            : workspace of sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN) bytes
  *                   (K and V are copied into it once per call in the kernel's
  *                   operand order; 2 * sizeof(K) bytes)

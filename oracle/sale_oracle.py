@@ -338,15 +338,24 @@ def quantize_qk_int8(q: np.ndarray, k: np.ndarray):
     return qc, qs, kc, ksc, mean
 
 
-def attention_block_int8qk(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_codes, s_k, v, mask_row):
+def attention_block_int8qk(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_codes, s_k, v, mask_row,
+                           q_blk=None, k_mean=None):
     """Rows of query block i with the attention weights taken from the 8-bit operands,
-    S = (Q~_i K~^T) s_q s_k[j] / sqrt(d) with K~ the codes of the smoothed K (exact integer products), and the
+    S' = (Q~_i K~^T) s_q s_k[j] / sqrt(d) with K~ the codes of the smoothed K (exact integer products), and the
     rest of Eq. 1 unchanged: causal and block mask, softmax, product with the unquantized V.
-    q_codes_blk int8 [64, d]; k_codes int8 [N, d]; s_k fp32 [N/64]; mask_row bool [N_k]."""
+    q_codes_blk int8 [64, d]; k_codes int8 [N, d]; s_k fp32 [N/64]; mask_row bool [N_k].
+    S' estimates the logits of K minus its mean key, i.e. Eq. 1's S minus q_r . k_mean / sqrt(d) per row; O does
+    not see that shift.  With q_blk (the unquantized rows, [64, d]) and k_mean ([d]) given, the returned lse has
+    the shift added back, so that it is the log-sum-exp of (the estimate of) Eq. 1's S; without them it is that
+    of S'."""
     assert geo.block_q == BLOCK8
     a = int_products(q_codes_blk, k_codes).astype(np.float64)                       # [64, N]
     s = a * float(s_q_i) * np.repeat(np.asarray(s_k, dtype=np.float64), BLOCK8)[None, :] / math.sqrt(geo.head_dim)
-    return attention_block_from_scores(geo, i, s, v, mask_row)
+    o, lse = attention_block_from_scores(geo, i, s, v, mask_row)
+    if q_blk is not None:
+        shift = np.asarray(q_blk, dtype=np.float64) @ np.asarray(k_mean, dtype=np.float64) / math.sqrt(geo.head_dim)
+        lse = lse + shift
+    return o, lse
 
 
 def dense_mask(geo: Geometry) -> np.ndarray:

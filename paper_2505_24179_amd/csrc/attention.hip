@@ -128,6 +128,7 @@ struct Qk8 {
   const u32x4* k8p;       // fragment order, 8 KB per 64 keys
   const float* q_scale;   // [q head][N / 64]
   const float* k_scale;   // [kv head][N / 64]
+  const float* k_mean;    // [kv head][128]: the mean key taken out of K before quantization
 };
 template <int WAVES, bool BK32, bool QK8>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
@@ -547,7 +548,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
           *(bf16x4*)(tile + (32 * nt + c) * kRowPad + 4 * h + 32 * dt + 8 * q4) = w;
         }
       }
-    if (lse && h == 0) lse[row] = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(l_tot) : -INFINITY;
+    if (lse && h == 0) {
+      float v = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(l_tot) : -INFINITY;
+      if constexpr (QK8) {
+        // The 8-bit logits are those of K minus its mean key, i.e. Eq. 1's logits of this row minus q_r . mean /
+        // sqrt(d) (which the softmax cancels in O); lse is reported for Eq. 1's S, so the shift goes back in.
+        const uint16_t* qr = q + row * kHeadDim;
+        const float* mean = q8o.k_mean + (size_t)u.kvh * kHeadDim;
+        float dot = 0.0f;
+        for (int ch = 0; ch < kHeadDim; ++ch) dot = __builtin_fmaf(bf16_bits_to_float(qr[ch]), mean[ch], dot);
+        v += dot * 0.08838834764831845f;
+      }
+      lse[row] = v;
+    }
   }
   if (!o32) {
     // (each wave reads back only its own tile: no barrier, LDS operations of a wave complete in order)
@@ -835,14 +848,14 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
                                                                                     (const uint16_t*)v, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const bool qk8 = (p->flags & SALE_FLAG_ATTN_INT8_QK) != 0;
-  Qk8 q8o = {nullptr, nullptr, nullptr, nullptr};
+  Qk8 q8o = {nullptr, nullptr, nullptr, nullptr, nullptr};
   if (qk8) {
     // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
     const uintptr_t end = (uintptr_t)(assign + n_units * (kMaskWordsMax / 2)) + 16 + kLaneLoadBytes;
     const Int8Operands w = carve_int8_operands(p, (void*)((end + 63) & ~(uintptr_t)63));
     const int rc = launch_int8_operands(p, q, k, w, true, st);
     if (rc != SALE_OK) return rc;
-    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale};
+    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale, w.k_mean};
   }
   const uint16_t* qq = (const uint16_t*)q;
   const bf16x8 *kpp = (const bf16x8*)kp, *vpp = (const bf16x8*)vp;

@@ -104,6 +104,37 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _expect(name: str, t, dtype, numel: int, optional: bool = False):
+    """Host-side check of one tensor argument before anything is launched: the C ABI takes raw device pointers
+    of contiguous buffers, so a wrong dtype, a strided view or a short buffer would be read or written out of
+    bounds on the GPU."""
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name}: required tensor is None")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: expected a device tensor, got {t.device}")
+    dtypes = dtype if isinstance(dtype, tuple) else (dtype,)
+    if t.dtype not in dtypes:
+        raise ValueError(f"{name}: expected dtype {dtypes}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: expected a contiguous tensor (the library takes no strides), got strides {t.stride()}")
+    if t.numel() != numel:
+        raise ValueError(f"{name}: expected {numel} elements for these parameters, got {t.numel()} (shape {tuple(t.shape)})")
+
+
+def _expect_ws(ws, need: int):
+    """-> the workspace's size in BYTES (whatever its dtype).  Size and alignment are the library's to judge
+    (SALE_ERR_WORKSPACE)."""
+    if ws is None or not ws.is_cuda or not ws.is_contiguous():
+        raise ValueError("workspace: expected a contiguous device tensor")
+    return ws.numel() * ws.element_size()
+
+
+def _qkv_numel(p: "Params"):
+    return (p.batch * p.n_q_heads * p.seq_len * p.head_dim, p.batch * p.n_kv_heads * p.seq_len * p.head_dim)
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -131,6 +162,11 @@ def quantize_qk(p: Params, q: torch.Tensor, k: torch.Tensor, out=None):
         ks = torch.empty(p.batch, p.n_kv_heads, p.seq_len // p.block_k, dtype=torch.float32, device=dev)
     else:
         q4, k4, qs, ks = out
+    nq, nk = _qkv_numel(p)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect("q4", q4, torch.uint8, nq // 2); _expect("k4", k4, torch.uint8, nk // 2)
+    _expect("q_scale", qs, torch.float32, p.batch * p.n_q_heads * (p.seq_len // p.block_q))
+    _expect("k_scale", ks, torch.float32, p.batch * p.n_kv_heads * (p.seq_len // p.block_k))
     _check(_lib.sale_quantize_qk(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(qs), _ptr(ks), _stream()))
     return q4, k4, qs, ks
 
@@ -150,9 +186,20 @@ def select(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, want_st
     need = workspace_bytes(p, WS_SELECT)
     if ws is None:
         ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+    nq, nk = _qkv_numel(p)
+    est16 = bool(p.flags & FLAG_SELECT_16BIT)          # the 16-bit estimate does not read the codes
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect("q4", q4, torch.uint8, nq // 2, optional=est16); _expect("k4", k4, torch.uint8, nk // 2, optional=est16)
+    _expect("q_scale", q_scale, torch.float32, p.batch * p.n_q_heads * p.n_q, optional=est16)
+    _expect("k_scale", k_scale, torch.float32, p.batch * p.n_kv_heads * p.n_k, optional=est16)
+    if tau.numel() not in (1, p.n_q_heads):
+        raise ValueError(f"tau: expected 1 or {p.n_q_heads} thresholds, got {tau.numel()}")
+    _expect("tau", tau, torch.float32, tau.numel())
+    _expect("block_mask", mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
+    _expect("row_counts", counts, torch.int32, p.batch * p.n_q_heads * p.n_q)
     _check(_lib.sale_select(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
                             _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), _ptr(m), _ptr(l),
-                            _ptr(ws), ws.numel(), _stream()))
+                            _ptr(ws), _expect_ws(ws, need), _stream()))
     return mask, counts, m, l
 
 
@@ -162,8 +209,13 @@ def sparse_attn(p: Params, q, k, v, block_mask, row_counts=None, want_lse: bool 
     lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_SPARSE_ATTN)), dtype=torch.uint8, device=q.device)
+    nq, nk = _qkv_numel(p)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
+    _expect("o", o, torch.bfloat16, nq)
+    _expect("block_mask", block_mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
+    _expect("row_counts", row_counts, torch.int32, p.batch * p.n_q_heads * p.n_q, optional=True)
     _check(_lib.sale_sparse_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(block_mask), _ptr(row_counts),
-                                 _ptr(o), _ptr(lse), _ptr(ws), 0 if ws is None else ws.numel(), _stream()))
+                                 _ptr(o), _ptr(lse), _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_SPARSE_ATTN)), _stream()))
     return o, lse
 
 
@@ -173,14 +225,19 @@ def dense_attn(p: Params, q, k, v, want_lse: bool = False, out=None, ws=None):
     lse = torch.empty(p.batch, p.n_q_heads, p.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_DENSE_ATTN)), dtype=torch.uint8, device=q.device)
+    nq, nk = _qkv_numel(p)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
+    _expect("o", o, torch.bfloat16, nq)
     _check(_lib.sale_dense_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
-                                _ptr(ws), ws.numel(), _stream()))
+                                _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_DENSE_ATTN)), _stream()))
     return o, lse
 
 
 def qk_int4_products(p: Params, q4, k4, q_head: int, q_block: int, k_block_begin: int, k_block_end: int):
     """-> int32 [block_q, (k_block_end - k_block_begin) * block_k]"""
-    out = torch.empty(p.block_q, (k_block_end - k_block_begin) * p.block_k, dtype=torch.int32, device=q4.device)
+    nq, nk = _qkv_numel(p)
+    _expect("q4", q4, torch.uint8, nq // 2); _expect("k4", k4, torch.uint8, nk // 2)
+    out = torch.empty(p.block_q, max(0, k_block_end - k_block_begin) * p.block_k, dtype=torch.int32, device=q4.device)
     _check(_lib.sale_qk_int4_products(ctypes.byref(p.c()), _ptr(q4), _ptr(k4), q_head, q_block,
                                       k_block_begin, k_block_end, _ptr(out), _stream()))
     return out
@@ -190,6 +247,8 @@ def attn_int8_operands(p: Params, q, k):
     """-> (q8 int8 [B,Hq,N,d], k8 int8 [B,Hkv,N,d], q_scale8 f32 [B,Hq,N/64], k_scale8 f32 [B,Hkv,N/64],
     k_mean f32 [B,Hkv,d]): the 8-bit operands of the quantized Computation-Pass (parity hook)."""
     dev = q.device
+    nq, nk = _qkv_numel(p)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
     q8 = torch.empty(p.batch, p.n_q_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
     k8 = torch.empty(p.batch, p.n_kv_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
     qs = torch.empty(p.batch, p.n_q_heads, p.seq_len // 64, dtype=torch.float32, device=dev)
@@ -204,11 +263,14 @@ def attn_int8_operands(p: Params, q, k):
 def calibrate_tau(p: Params, q, k, v, tau0: float = 0.008, theta: float = 0.4, max_halvings: int = 8, ws=None):
     """-> (tau f32 [Hq], err f32 [Hq], halvings i32 [Hq]); synchronises the current stream."""
     dev = q.device
+    nq, nk = _qkv_numel(p)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
     tau = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
     err = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
     halv = torch.empty(p.n_q_heads, dtype=torch.int32, device=dev)
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_CALIBRATE)), dtype=torch.uint8, device=dev)
     _check(_lib.sale_calibrate_tau(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), tau0, theta, max_halvings,
-                                   _ptr(tau), _ptr(err), _ptr(halv), _ptr(ws), ws.numel(), _stream()))
+                                   _ptr(tau), _ptr(err), _ptr(halv), _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_CALIBRATE)),
+                                   _stream()))
     return tau, err, halv

@@ -103,3 +103,37 @@ def test_argument_validation_launches_nothing(sale):
     assert prod(ctypes.byref(good.c()), f, f, 0, 0, 2, 1, f, None) == -2
     assert prod(ctypes.byref(good.c()), f, f, 0, 0, 0, 5, f, None) == -2
     assert prod(ctypes.byref(good.c()), f, f, 0, 0, 1, 1, f, None) == 0    # empty range: nothing to do
+
+
+def test_binding_rejects_wrong_tensors_on_the_host():
+    """The binding checks device, dtype, contiguity and element count of every tensor before marshalling: the C
+    ABI takes raw pointers of contiguous buffers, so a CPU tensor, a transposed view or a short buffer must not
+    reach a kernel.  (Runs without a GPU: the checks come before any library call.)"""
+    import torch
+    sale = pytest.importorskip("paper_2505_24179_amd.sale")
+    p = sale.Params(1, 2, 1, 128)
+    q = torch.zeros(1, 2, 128, 128, dtype=torch.bfloat16)
+    k = torch.zeros(1, 1, 128, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="device tensor"):
+        sale._expect("q", q, torch.bfloat16, q.numel())
+    meta_q = torch.zeros(1, 128, 2, 128, dtype=torch.bfloat16, device="meta").transpose(1, 2)     # [B][N][H][d] viewed as [B][H][N][d]
+    assert not meta_q.is_contiguous()
+
+    class FakeCuda:          # what _expect looks at, with is_cuda forced on
+        def __init__(self, t): self.t = t
+        is_cuda = True
+        dtype = property(lambda self: self.t.dtype)
+        shape = property(lambda self: self.t.shape)
+        def is_contiguous(self): return self.t.is_contiguous()
+        def stride(self): return self.t.stride()
+        def numel(self): return self.t.numel()
+    with pytest.raises(ValueError, match="contiguous"):
+        sale._expect("q", FakeCuda(meta_q), torch.bfloat16, q.numel())
+    with pytest.raises(ValueError, match="dtype"):
+        sale._expect("q", FakeCuda(q.float()), torch.bfloat16, q.numel())
+    with pytest.raises(ValueError, match="elements"):
+        sale._expect("k", FakeCuda(k), torch.bfloat16, q.numel())
+    with pytest.raises(ValueError, match="None"):
+        sale._expect("q", None, torch.bfloat16, 1)
+    sale._expect("row_counts", None, torch.int32, 1, optional=True)
+    sale._expect("q", FakeCuda(q), torch.bfloat16, q.numel())

@@ -71,14 +71,15 @@ def test_int8_operands_zero_block_and_shifted_keys(sale):
 
 def _oracle_int8(w, geo, q, k, v, ops, masks):
     qc, qs, kc, ks, mean = ops
-    vf = f32(v)
+    vf, qf = f32(v), f32(q)
     o = np.zeros((w.n_q_heads, w.seq_len, w.head_dim))
     lse = np.zeros((w.n_q_heads, w.seq_len))
     for h in range(w.n_q_heads):
         g = h // w.group
         for i in range(geo.n_q):
             rs = slice(i * 64, (i + 1) * 64)
-            o[h, rs], lse[h, rs] = so.attention_block_int8qk(geo, i, qc[h][rs], qs[h, i], kc[g], ks[g], vf[g], masks[h][i])
+            o[h, rs], lse[h, rs] = so.attention_block_int8qk(geo, i, qc[h][rs], qs[h, i], kc[g], ks[g], vf[g], masks[h][i],
+                                                               q_blk=qf[h][rs], k_mean=mean[g])
     return o, lse
 
 

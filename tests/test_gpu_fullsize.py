@@ -199,14 +199,15 @@ def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
             np.testing.assert_array_equal(mean[0, g].cpu().numpy().view(np.uint32), omean[0].view(np.uint32))
             np.testing.assert_array_equal(k8[0, g].cpu().numpy(), kc[0])
             np.testing.assert_array_equal(ks8[0, g].cpu().numpy().view(np.uint32), oks[0].view(np.uint32))
-            kq = {g: (kc[0], oks[0], v[g].float().numpy())}
-        kc, oks, vf = kq[g]
+            kq = {g: (kc[0], oks[0], v[g].float().numpy(), omean[0])}
+        kc, oks, vf, kmean = kq[g]
         rs = slice(i * 64, (i + 1) * 64)
         qc, oqs = so.quantize_blocks(q[h, rs].float().numpy()[None], 64, 127)
         np.testing.assert_array_equal(q8[0, h, rs].cpu().numpy(), qc[0])
         assert qs8[0, h, i].cpu().numpy().view(np.uint32) == oqs[0, 0].view(np.uint32)
         got_row = words_to_bool(mask[0, h, i].cpu().numpy(), p.n_k)
-        ref_s, ref_lse = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, got_row)
+        ref_s, ref_lse = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, got_row,
+                                                   q_blk=q[h, rs].float().numpy(), k_mean=kmean)
         ref_d, _ = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, np.arange(geo.n_k) <= i)
         ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"int8 sparse {name} h{h} i{i}")
         md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"int8 dense {name} h{h} i{i}")
@@ -264,8 +265,31 @@ def test_full_size_properties_over_every_row_128k(sale, bk):
     o_all = o_all.clone()
     o_dense, lse_dense = sale.dense_attn(p, qd, kd, vd, want_lse=True, ws=ws)
     assert torch.equal(o_all, o_dense) and torch.equal(lse_all, lse_dense)
-    o_sp, lse_sp = sale.sparse_attn(p, qd, kd, vd, *masks[0.004], want_lse=True, ws=ws)
-    assert torch.isfinite(o_sp.float()).all() and torch.isfinite(lse_sp).all()
+    # Under the real mask: every row through the windowed, balanced path (row_counts given) against the same
+    # row through the plain one-sweep path (no counts: no ordering, no windows, no tables).  Both outputs
+    # start as NaN, so a unit that a table or a tail rank dropped, or that was written from stale state, shows.
+    o_sp = torch.full_like(qd, float("nan"))
+    lse_sp = torch.full((1, w.n_q_heads, w.seq_len), float("nan"), dtype=torch.float32, device=dev)
+    lib = sale.raw()
+    import ctypes
+    def run(counts_t, o_t, lse_t):
+        rc = lib.sale_sparse_attn(ctypes.byref(p.c()), qd.data_ptr(), kd.data_ptr(), vd.data_ptr(), masks[0.004][0].data_ptr(),
+                                  None if counts_t is None else counts_t.data_ptr(), o_t.data_ptr(), lse_t.data_ptr(),
+                                  ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        assert rc == 0
+    run(masks[0.004][1], o_sp, lse_sp)
+    o_one = torch.full_like(qd, float("nan"))
+    lse_one = torch.full_like(lse_sp, float("nan"))
+    run(None, o_one, lse_one)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o_sp.float()).all() and torch.isfinite(lse_sp).all()          # every unit was written
+    assert torch.isfinite(o_one.float()).all() and torch.isfinite(lse_one).all()
+    d_win = (o_sp.float() - o_one.float()).abs()
+    # (the two paths add the same blocks in the same order; they differ only where a long row's accumulators
+    # were parked between windows, which is exact, so the outputs agree far inside the parity bar)
+    assert float(d_win.max()) <= 2e-2 and float(d_win.mean()) <= 2e-4, (float(d_win.max()), float(d_win.mean()))
+    assert float((lse_sp - lse_one).abs().max()) <= 2 * LSE_ATOL
+    print(f"[128k 64x{bk}] windowed vs one-sweep over every row: max {float(d_win.max()):.3g} mean {float(d_win.mean()):.3g}")
     mass = torch.exp(lse_sp - lse_dense)
     assert float(mass.max()) <= 1.0 + 2 * LSE_ATOL and float(mass.min()) > 0.0
     print(f"[128k 64x{bk}] kept probability mass: min {float(mass.min()):.3f} mean {float(mass.mean()):.4f}")
@@ -300,3 +324,76 @@ def test_many_kv_heads_beyond_the_balancing_table(sale):
         row = words_to_bool(mask[b, 0, i].cpu().numpy(), p.n_k)
         ref, _ = so.attention_block(geo, i, qb[b, 0, rs].float().cpu().numpy(), kf, vf, row)
         check_output(o_win[b, 0, rs].float().cpu().numpy(), ref, f"264 lanes b{b} i{i}")
+
+
+def _predict_balance_overflow(mask_bool, counts, n_qb, lanes, win_lo, win_hi, min_count):
+    """The placement rule of the window tables, restated on the host from its description (a head whose work in
+    the window exceeds the mean sheds n_in * (w - mean) / w units to the heads that lack work, in proportion to
+    what they lack): does some lane end up with more entries than it has slots (= units per KV head)?"""
+    work, n_in = [], []
+    for l in range(lanes):
+        w_l = n_l = 0
+        for i in range(n_qb):
+            if counts[l, i] <= min_count or win_lo > i:
+                continue
+            c = int(mask_bool[l, i, win_lo:min(win_hi, i + 1)].sum())
+            if c > 0 or win_hi > i:
+                n_l += 1
+                w_l += c
+        work.append(w_l); n_in.append(n_l)
+    target = sum(work) / lanes
+    shed = [int(n_in[l] * (work[l] - target) / work[l]) if work[l] > target else 0 for l in range(lanes)]
+    lack = [max(0.0, target - work[l]) for l in range(lanes)]
+    total = sum(shed)
+    recv, run = [], 0.0
+    for l in range(lanes):
+        lo = int(total * (run / sum(lack)))
+        run += lack[l]
+        recv.append(lo)
+    recv.append(total)
+    return any(n_in[l] - shed[l] + recv[l + 1] - recv[l] > n_qb for l in range(lanes)), n_in, shed
+
+
+def test_balance_table_overflow_falls_back_to_lane_equals_head(sale):
+    """One KV head whose long rows keep a single block in the second window next to three heads that keep everything
+    there: the light head's lane would receive more shed units than it has slots, so the window's table falls back
+    to lane = KV head.  The result must be that of the one-sweep path, every unit written once, and equal to the
+    oracle on sampled units."""
+    n, hq = 40960, 4                                       # 640 query blocks, 5 windows of 128 key blocks
+    g = torch.Generator().manual_seed(77)
+    q = torch.randn(hq, n, 128, generator=g).bfloat16()
+    k = torch.randn(hq, n, 128, generator=g).bfloat16()
+    v = torch.randn(hq, n, 128, generator=g).bfloat16()
+    p = sale.Params(1, hq, hq, n)
+    n_qb = p.n_q
+    keep = np.zeros((hq, n_qb, n_qb), dtype=bool)
+    tri = np.tril(np.ones((n_qb, n_qb), dtype=bool))
+    keep[1:] = tri
+    keep[0] = tri
+    keep[0, :, 129:256] = False                            # head 0: of window 1 (blocks 128..255) only block 128
+    keep[0][np.arange(n_qb), np.arange(n_qb)] = True       # (the diagonal block stays)
+    keep[0] &= tri
+    counts_np = keep.sum(-1).astype(np.int32)
+    overflow, n_in, shed = _predict_balance_overflow(keep, counts_np, n_qb, hq, 128, 256, 192)
+    assert overflow, (n_in, shed)                          # the case does reach the fallback
+    words = np.zeros((hq, n_qb, p.words), dtype=np.uint64)
+    for j in range(n_qb):
+        words[:, :, j // 64] |= keep[:, :, j].astype(np.uint64) << np.uint64(j % 64)
+    dev = torch.device("cuda:0")
+    mask = torch.from_numpy(words.view(np.int64)).unsqueeze(0).to(dev)
+    counts = torch.from_numpy(counts_np).unsqueeze(0).to(dev)
+    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+    ws = torch.empty(sale.workspace_bytes(p, sale.WS_SPARSE_ATTN), dtype=torch.uint8, device=dev)
+    o_win = torch.full_like(qd, float("nan"))
+    o_one = torch.full_like(qd, float("nan"))
+    sale.sparse_attn(p, qd, kd, vd, mask, counts, out=o_win, ws=ws)
+    sale.sparse_attn(p, qd, kd, vd, mask, None, out=o_one, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o_win.float()).all() and torch.isfinite(o_one.float()).all()
+    d = (o_win.float() - o_one.float()).abs()
+    assert float(d.max()) <= 2e-2 and float(d.mean()) <= 2e-4
+    geo = so.Geometry(n, 128)
+    for h, i in ((0, n_qb - 1), (0, 330), (2, n_qb - 1), (3, 200)):
+        rs = slice(i * 64, (i + 1) * 64)
+        ref, _ = so.attention_block(geo, i, q[h, rs].float().numpy(), k[h].float().numpy(), v[h].float().numpy(), keep[h, i])
+        check_output(o_win[0, h, rs].float().cpu().numpy(), ref, f"overflow fallback h{h} i{i}")

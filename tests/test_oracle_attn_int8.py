@@ -102,6 +102,32 @@ def test_int8_scores_within_the_quantization_bound_of_the_exact_ones():
     assert 1e-5 < worst < 2e-2
 
 
+def test_int8_lse_with_the_shift_added_back_is_the_lse_of_eq1():
+    """The 8-bit logits are those of K minus its mean key: lse(S') = lse(S) - q_r . mean / sqrt(d) exactly when
+    nothing is lost to quantization, and within the largest logit error of the row otherwise (a log-sum-exp moves
+    by at most the largest change of its arguments).  With q_blk and k_mean given the oracle adds the shift back."""
+    n, d = 512, 128
+    q, k, v = _rand(n, d, 11, shift=1.5)
+    qc, qs, kc, ks, mean = so.quantize_qk_int8(q[None], k[None])
+    assert np.abs(mean).max() > 1.0                               # the shift is not negligible here
+    kprime = k.astype(np.float64) - mean[0].astype(np.float64)
+    geo = so.Geometry(n, d, 64, 64, 1, 2)
+    for i in (0, 2, 7):
+        rs = slice(i * 64, (i + 1) * 64)
+        row = so.dense_mask(geo)[i]
+        _, l_raw = so.attention_block_int8qk(geo, i, qc[0][rs], qs[0, i], kc[0], ks[0], v, row)
+        _, l_fix = so.attention_block_int8qk(geo, i, qc[0][rs], qs[0, i], kc[0], ks[0], v, row, q_blk=q[rs], k_mean=mean[0])
+        _, l_exact = so.attention_block(geo, i, q[rs], k, v, row)
+        shift = q[rs].astype(np.float64) @ mean[0].astype(np.float64) / math.sqrt(d)
+        np.testing.assert_allclose(l_fix - l_raw, shift, rtol=0, atol=1e-12)
+        assert np.abs(shift).max() > 0.5 and np.abs(l_raw - l_exact).max() > 0.5     # without the shift lse is far off
+        sq, sk = float(qs[0, i]), np.repeat(ks[0].astype(np.float64), 64)
+        bound = (0.5 * sq * np.abs(kprime).sum(1)[None, :] + 0.5 * sk[None, :] * np.abs(q[rs]).sum(1)[:, None]
+                 + d * sq * sk[None, :] / 4) / math.sqrt(d)
+        assert np.all(np.abs(l_fix - l_exact) <= bound.max(axis=1) * (1 + 1e-9))
+        assert np.abs(l_fix - l_exact).max() < 0.05
+
+
 def test_attention_block_from_scores_is_attention_block():
     q, k, v = _rand(256, 32, 6)
     geo = so.Geometry(256, 32, 64, 32, 1, 2)
