@@ -13,7 +13,8 @@
  *   workspace (16-byte aligned) whose size sale_workspace_bytes() reports.
  * - Calls are asynchronous on the given hipStream_t (passed as void*; NULL =
  *   the default stream), never synchronise (sale_calibrate_tau excepted) and
- *   keep no global state.
+ *   keep no global state (sale_select_static excepted: its scratch memory is a
+ *   static device array of the library).
  * - All tensors are contiguous, row-major, last dimension fastest:
  *     Q, O : bf16 [batch][n_q_heads ][seq_len][head_dim]
  *     K, V : bf16 [batch][n_kv_heads][seq_len][head_dim]
@@ -152,6 +153,31 @@ int sale_select(const sale_params_t* p, const void* q, const void* k,
                 uint64_t* block_mask, int32_t* row_counts,
                 float* m_out, float* l_out,
                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * sale_select for callers that cannot allocate device memory or own a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and checks as sale_select, without the
+ * workspace: the scratch memory is a static device array inside the library,
+ * SALE_SELECT_STATIC_MAX_BYTES large, that every GPU the library runs on holds
+ * until the process ends.  The call allocates and frees nothing.
+ * - Geometries whose sale_workspace_bytes(p, SALE_WS_SELECT) exceeds
+ *   SALE_SELECT_STATIC_MAX_BYTES return SALE_ERR_WORKSPACE and launch nothing
+ *   (64 MiB covers 32 query / 8 KV heads up to 16384 tokens).
+ * - The device whose stream is passed must be the current device.  The first
+ *   call on a device looks up that device's copy of the array.
+ * - All calls on one GPU share that GPU's array: calls that overlap in time on
+ *   one GPU (different streams or threads) race.  Nothing in the array has to
+ *   be cleared between calls: every byte a kernel reads is written earlier in
+ *   the same call.
+ */
+#define SALE_SELECT_STATIC_MAX_BYTES (64u << 20)
+int sale_select_static(const sale_params_t* p, const void* q, const void* k,
+                       const uint8_t* q4, const uint8_t* k4,
+                       const float* q_scale, const float* k_scale,
+                       const float* tau, int32_t tau_len,
+                       uint64_t* block_mask, int32_t* row_counts,
+                       float* m_out, float* l_out, void* stream);
 
 /*
  * Computation-Pass (Sec. 3.1, Eq. 1 with the block mask of Eq. 2):

@@ -11,6 +11,8 @@
 //
 // CDNA4 has no int4 MFMA: the integer products run, exactly, on the FP6 MFMA
 // (see below).
+#include <mutex>
+
 #include "sale_common.h"
 
 namespace sale {
@@ -425,20 +427,29 @@ int launch_select(const Geo& g, bool est16, const void* q, const void* k, const 
 
 }  // namespace
 
-extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k, const uint8_t* q4, const uint8_t* k4,
-                           const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len,
-                           uint64_t* block_mask, int32_t* row_counts, float* m_out, float* l_out, void* ws,
-                           size_t ws_bytes, void* stream) {
+namespace {
+
+// Checks shared by the two Selection-Pass entry points (everything but the workspace).
+int check_select_args(const sale_params_t* p, const void* q, const void* k, const uint8_t* q4, const uint8_t* k4,
+                      const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len,
+                      const uint64_t* block_mask, const int32_t* row_counts) {
   if (!p || !q || !k || !tau || !block_mask || !row_counts) return SALE_ERR_NULL_ARG;
   const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
   if (!est16 && (!q4 || !k4 || !q_scale || !k_scale)) return SALE_ERR_NULL_ARG;
-  int rc = validate_common(p, kGeomPath);
+  const int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   if (tau_len != 1 && tau_len != p->n_q_heads) return SALE_ERR_BAD_SHAPE;
-  const size_t need = sale_workspace_bytes(p, SALE_WS_SELECT);
-  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
+  return SALE_OK;
+}
+
+// The Selection-Pass on a workspace that has been checked.  Every byte of the workspace that a kernel reads is
+// written earlier in the same call (thresholds by the statistics kernel, operand copies by the packing kernel),
+// so nothing in it has to be cleared.
+int run_select(const sale_params_t* p, const void* q, const void* k, const uint8_t* q4, const uint8_t* k4,
+               const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len, uint64_t* block_mask,
+               int32_t* row_counts, float* m_out, float* l_out, void* ws, hipStream_t st) {
+  const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
   const Geo g = make_geo(p);
-  hipStream_t st = (hipStream_t)stream;
   float* thr = (float*)ws;
   uint8_t* q6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
   uint8_t* k6 = q6 + (size_t)g.n_qh * (g.seq / 32) * kX6GroupBytes;
@@ -451,6 +462,62 @@ extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k,
                                        row_counts, m_out, l_out, st)
                     : launch_select<1>(g, est16, q, k, q6, k6, q_scale, k_scale, tau, tau_len, thr, thr, block_mask,
                                        row_counts, m_out, l_out, st);
+}
+
+}  // namespace
+
+extern "C" int sale_select(const sale_params_t* p, const void* q, const void* k, const uint8_t* q4, const uint8_t* k4,
+                           const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len,
+                           uint64_t* block_mask, int32_t* row_counts, float* m_out, float* l_out, void* ws,
+                           size_t ws_bytes, void* stream) {
+  const int rc = check_select_args(p, q, k, q4, k4, q_scale, k_scale, tau, tau_len, block_mask, row_counts);
+  if (rc != SALE_OK) return rc;
+  const size_t need = sale_workspace_bytes(p, SALE_WS_SELECT);
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
+  return run_select(p, q, k, q4, k4, q_scale, k_scale, tau, tau_len, block_mask, row_counts, m_out, l_out, ws,
+                    (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// Selection-Pass for callers that cannot allocate: the workspace is a static device array of the library.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SALE_SELECT_STATIC_MAX_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];      // per device: the address of that GPU's copy of `scratch`
+
+// Device address of the current device's copy of `scratch` (in host code the array's name is only a handle:
+// the address has to be asked for, once per device, with that device current).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SALE_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SALE_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SALE_OK;
+}
+
+}  // namespace
+
+extern "C" int sale_select_static(const sale_params_t* p, const void* q, const void* k, const uint8_t* q4,
+                                  const uint8_t* k4, const float* q_scale, const float* k_scale, const float* tau,
+                                  int32_t tau_len, uint64_t* block_mask, int32_t* row_counts, float* m_out,
+                                  float* l_out, void* stream) {
+  int rc = check_select_args(p, q, k, q4, k4, q_scale, k_scale, tau, tau_len, block_mask, row_counts);
+  if (rc != SALE_OK) return rc;
+  if (sale_workspace_bytes(p, SALE_WS_SELECT) > (size_t)SALE_SELECT_STATIC_MAX_BYTES) return SALE_ERR_WORKSPACE;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != SALE_OK) return rc;
+  return run_select(p, q, k, q4, k4, q_scale, k_scale, tau, tau_len, block_mask, row_counts, m_out, l_out, ws,
+                    (hipStream_t)stream);
 }
 
 extern "C" int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, const uint8_t* k4, int32_t q_head,

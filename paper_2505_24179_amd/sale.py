@@ -74,6 +74,7 @@ _SIGS = {
     "sale_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "sale_quantize_qk": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "sale_select": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sale_select_static": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "sale_sparse_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
@@ -201,6 +202,27 @@ def select(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, want_st
                             _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), _ptr(m), _ptr(l),
                             _ptr(ws), _expect_ws(ws, need), _stream()))
     return mask, counts, m, l
+
+
+SELECT_STATIC_MAX_BYTES = 64 << 20
+
+
+def select_static(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, out):
+    """sale_select on the library's static scratch: allocates nothing, so `out` = (block_mask, row_counts) is
+    required.  -> (block_mask, row_counts)"""
+    mask, counts = out
+    nq, nk = _qkv_numel(p)
+    est16 = bool(p.flags & FLAG_SELECT_16BIT)
+    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect("q4", q4, torch.uint8, nq // 2, optional=est16); _expect("k4", k4, torch.uint8, nk // 2, optional=est16)
+    _expect("q_scale", q_scale, torch.float32, p.batch * p.n_q_heads * p.n_q, optional=est16)
+    _expect("k_scale", k_scale, torch.float32, p.batch * p.n_kv_heads * p.n_k, optional=est16)
+    _expect("tau", tau, torch.float32, tau.numel())
+    _expect("block_mask", mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
+    _expect("row_counts", counts, torch.int32, p.batch * p.n_q_heads * p.n_q)
+    _check(_lib.sale_select_static(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
+                                   _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), None, None, _stream()))
+    return mask, counts
 
 
 def sparse_attn(p: Params, q, k, v, block_mask, row_counts=None, want_lse: bool = False, out=None, ws=None):

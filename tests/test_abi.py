@@ -137,3 +137,18 @@ def test_binding_rejects_wrong_tensors_on_the_host():
         sale._expect("q", None, torch.bfloat16, 1)
     sale._expect("row_counts", None, torch.int32, 1, optional=True)
     sale._expect("q", FakeCuda(q), torch.bfloat16, q.numel())
+
+
+def test_static_scratch_select_checks_before_touching_the_gpu(sale):
+    import ctypes
+    lib = sale.raw()
+    f = ctypes.c_void_p(0x1000)        # never dereferenced
+    too_big = sale.Params(1, 32, 8, 32768)
+    assert sale.workspace_bytes(too_big, sale.WS_SELECT) > sale.SELECT_STATIC_MAX_BYTES
+    assert lib.sale_select_static(ctypes.byref(too_big.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None) == -4
+    fits = sale.Params(1, 32, 8, 16384)
+    assert sale.workspace_bytes(fits, sale.WS_SELECT) <= sale.SELECT_STATIC_MAX_BYTES
+    assert lib.sale_select_static(ctypes.byref(fits.c()), f, f, f, f, f, f, None, 1, f, f, None, None, None) == -1
+    assert lib.sale_select_static(ctypes.byref(fits.c()), f, f, f, f, f, f, f, 5, f, f, None, None, None) == -2
+    bad = sale.Params(1, 32, 8, 16384, block_q=32)
+    assert lib.sale_select_static(ctypes.byref(bad.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None) == -3
