@@ -26,6 +26,21 @@ PEAK_FP6_TFLOPS = 10100.0     # MI355X dense fp6 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def _oracle_threads() -> int:
+    """Threads the oracle's numpy work really runs on: the thread count of numpy's BLAS (its matrix products are
+    where the time goes; the element-wise parts are single-threaded), capped by the cores this process may use."""
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [i["num_threads"] for i in threadpool_info() if i.get("user_api") == "blas"]
+        return min(max(blas), avail) if blas else 1
+    except Exception:
+        return 1
+
+
 def cpu_baseline(w, q, k, v, budget_units: int, seed: int = 1234, block_k: int = 64, segment: int = 0):
     """Times the CPU oracle (as it stands) on a seeded sample of (head, query
     block) units of the same workload and extrapolates to the whole layer."""
@@ -55,10 +70,11 @@ def cpu_baseline(w, q, k, v, budget_units: int, seed: int = 1234, block_k: int =
     return {
         "value": dt / len(units) * total_units * 1e3,
         "unit": "ms",
-        "cores": torch.get_num_threads(),
+        "cores": _oracle_threads(),
         "kind": "oracle",
         "sample": f"{len(units)} of {total_units} (head, 64-row query block) units drawn uniformly (seed {seed}) from the "
-                  f"same workload, measured {dt:.1f} s; value = sample mean x {total_units} units (extrapolated)",
+                  f"same workload, measured {dt:.1f} s; value = sample mean x {total_units} units (extrapolated); "
+                  f"host reports {os.cpu_count()} CPUs, numpy BLAS threads as in `cores`",
     }
 
 
@@ -76,6 +92,8 @@ def main() -> int:
     ap.add_argument("--attn-int8-qk", action="store_true",
                     help="quantized Computation-Pass (Sec. 3.4): 8-bit Q, K in the first product of sparse AND dense attention")
     ap.add_argument("--cpu-units", type=int, default=96, help="oracle sample size (0 = skip the CPU baseline)")
+    ap.add_argument("--no-lengths", dest="lengths", action="store_false",
+                    help="skip the 32K and 64K legs that the default 128K run adds (object `lengths`)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards by KV head without communication, "
@@ -88,90 +106,109 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    dev = torch.device("cuda:0")
+    flags = (sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0) | (sale.FLAG_ATTN_INT8_QK if args.attn_int8_qk else 0)
+
+    def measure(w, steps, warmup, dense_steps):
+        """One workload: K timed steps of quantize -> select -> sparse attention (HIP events around every stage on
+        the launch stream), then the dense kernel.  -> (figures, host tensors q, k, v)"""
+        t_gen = time.perf_counter()
+        q, k, v = inputs.make_inputs(w)
+        t_gen = time.perf_counter() - t_gen
+        p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=args.block_k, flags=flags)
+        qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
+        tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
+        # all outputs and the workspaces are allocated once, outside the timed region
+        q4 = torch.empty(1, w.n_q_heads, w.seq_len, 64, dtype=torch.uint8, device=dev)
+        k4 = torch.empty(1, w.n_kv_heads, w.seq_len, 64, dtype=torch.uint8, device=dev)
+        qs = torch.empty(1, w.n_q_heads, p.n_q, dtype=torch.float32, device=dev)
+        ks = torch.empty(1, w.n_kv_heads, p.n_k, dtype=torch.float32, device=dev)
+        mask = torch.empty(1, w.n_q_heads, p.n_q, p.words, dtype=torch.int64, device=dev)
+        counts = torch.empty(1, w.n_q_heads, p.n_q, dtype=torch.int32, device=dev)
+        o = torch.empty_like(qd)
+        ws_sel = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SELECT)), dtype=torch.uint8, device=dev)
+        ws_att = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)), dtype=torch.uint8, device=dev)
+
+        def step(ev=None):
+            if ev: ev[0].record()
+            sale.quantize_qk(p, qd, kd, out=(q4, k4, qs, ks))
+            if ev: ev[1].record()
+            sale.select(p, qd, kd, q4, k4, qs, ks, tau, out=(mask, counts), ws=ws_sel)
+            if ev: ev[2].record()
+            sale.sparse_attn(p, qd, kd, vd, mask, counts, out=o, ws=ws_att)
+            if ev: ev[3].record()
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for s in range(steps):
+            step(evs[s])
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        quant_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / steps
+        select_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
+        sparse_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / steps
+        dense_ms = None
+        if dense_steps > 0:      # the denominator
+            sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(dense_steps):
+                sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
+            b.record()
+            torch.cuda.synchronize()
+            dense_ms = a.elapsed_time(b) / dense_steps
+
+        # a "pair" is one (query block, key block) tile: 64 x b_k logits
+        n_q, kpq = p.n_q, 64 // args.block_k
+        causal_pairs = w.n_q_heads * sum((i + 1) * kpq for i in range(n_q))
+        kept_pairs = int(counts.sum().item())
+        flop_pair = 4.0 * 64 * args.block_k * 128
+        # (the segment rule moves at most 3 blocks per row from the middle to the local area: not subtracted)
+        middle_pairs = sum(max(0, (i + 1) * kpq - p.sink_blocks - p.local_blocks) for i in range(n_q)) * w.n_q_heads
+        quant_bytes = (w.n_q_heads + w.n_kv_heads) * w.seq_len * (256 + 64) + (w.n_q_heads + w.n_kv_heads) * n_q * 4
+        bf16_peak = PEAK_BF16_TFLOPS
+        if args.attn_int8_qk:       # the first product runs at the int8 MFMA rate, the second at the bf16 rate
+            bf16_peak = 2.0 / (1.0 / PEAK_BF16_TFLOPS + 1.0 / PEAK_INT8_TOPS)
+        kernels = {
+            "quantize": {"bound": "hbm", "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
+                         "unit": "GB/s", "ms": quant_ms},
+            "select": {"bound": "mfma", "achieved": middle_pairs * 2.0 * 64 * args.block_k * 128 / (select_ms * 1e-3) / 1e12,
+                       "peak": PEAK_FP6_TFLOPS, "unit": "TFLOP/s", "ms": select_ms},
+            "sparse_attn": {"bound": "mfma", "achieved": kept_pairs * flop_pair / (sparse_ms * 1e-3) / 1e12,
+                            "peak": bf16_peak, "unit": "TFLOP/s", "ms": sparse_ms},
+        }
+        if dense_ms:
+            kernels["dense_attn"] = {"bound": "mfma", "achieved": causal_pairs * flop_pair / (dense_ms * 1e-3) / 1e12,
+                                     "peak": bf16_peak, "unit": "TFLOP/s", "ms": dense_ms}
+        for kv in kernels.values():
+            kv["frac"] = kv["achieved"] / kv["peak"]
+        sale_ms = quant_ms + select_ms + sparse_ms
+        # the dense time of a kernel AT the 60 % target: the overhead bound must not lean on a slow denominator
+        dense60_ms = causal_pairs * flop_pair / (0.6 * bf16_peak * 1e12) * 1e3
+        fig = {
+            "sale_ms": sale_ms, "wall_ms": wall_ms, "input_gen_s": t_gen,
+            "stages_ms": {"quantize": quant_ms, "select": select_ms, "sparse_attn": sparse_ms, "dense_attn": dense_ms},
+            "density": kept_pairs / causal_pairs,
+            "select_overhead_pct": None if not dense_ms else 100.0 * (quant_ms + select_ms) / dense_ms,
+            "select_overhead_pct_of_dense_at_60pct_peak": 100.0 * (quant_ms + select_ms) / dense60_ms,
+            "computation_pass_speedup": None if not dense_ms else dense_ms / sparse_ms,
+            "end_to_end_speedup": None if not dense_ms else dense_ms / sale_ms,
+            "effective_tflops": causal_pairs * flop_pair / (sale_ms * 1e-3) / 1e12,
+            "tokens_per_s": w.seq_len / (sale_ms * 1e-3),
+            "kernels": kernels,
+        }
+        return fig, (q, k, v)
+
     w = inputs.WORKLOADS[args.workload]
     if args.tau is not None:
         from dataclasses import replace
         w = replace(w, tau=args.tau)
-    t_gen = time.perf_counter()
-    q, k, v = inputs.make_inputs(w)
-    t_gen = time.perf_counter() - t_gen
-    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, block_k=args.block_k,
-                    flags=(sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0) |
-                          (sale.FLAG_ATTN_INT8_QK if args.attn_int8_qk else 0))
-    dev = torch.device("cuda:0")
-    qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
-    tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
-
-    # all outputs and the workspace are allocated once, outside the timed region
-    q4 = torch.empty(1, w.n_q_heads, w.seq_len, 64, dtype=torch.uint8, device=dev)
-    k4 = torch.empty(1, w.n_kv_heads, w.seq_len, 64, dtype=torch.uint8, device=dev)
-    qs = torch.empty(1, w.n_q_heads, p.n_q, dtype=torch.float32, device=dev)
-    ks = torch.empty(1, w.n_kv_heads, p.n_k, dtype=torch.float32, device=dev)
-    mask = torch.empty(1, w.n_q_heads, p.n_q, p.words, dtype=torch.int64, device=dev)
-    counts = torch.empty(1, w.n_q_heads, p.n_q, dtype=torch.int32, device=dev)
-    o = torch.empty_like(qd)
-    ws_sel = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SELECT)), dtype=torch.uint8, device=dev)
-    ws_att = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)), dtype=torch.uint8, device=dev)
-
-    def step(ev=None):
-        if ev: ev[0].record()
-        sale.quantize_qk(p, qd, kd, out=(q4, k4, qs, ks))
-        if ev: ev[1].record()
-        sale.select(p, qd, kd, q4, k4, qs, ks, tau, out=(mask, counts), ws=ws_sel)
-        if ev: ev[2].record()
-        sale.sparse_attn(p, qd, kd, vd, mask, counts, out=o, ws=ws_att)
-        if ev: ev[3].record()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(evs[s])
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    quant_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    select_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    sparse_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
-
-    # dense denominator
-    dense_ms = None
-    if args.dense_steps > 0:
-        sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(args.dense_steps):
-            sale.dense_attn(p, qd, kd, vd, out=o, ws=ws_att)
-        b.record()
-        torch.cuda.synchronize()
-        dense_ms = a.elapsed_time(b) / args.dense_steps
-
-    # a "pair" is one (query block, key block) tile: 64 x b_k logits
-    n_q, kpq = p.n_q, 64 // args.block_k
-    causal_pairs = w.n_q_heads * sum((i + 1) * kpq for i in range(n_q))
-    kept_pairs = int(counts.sum().item())
-    density = kept_pairs / causal_pairs
-    flop_pair = 4.0 * 64 * args.block_k * 128
-    # (the segment rule moves at most 3 blocks per row from the middle to the local area: not subtracted)
-    middle_pairs = sum(max(0, (i + 1) * kpq - p.sink_blocks - p.local_blocks) for i in range(n_q)) * w.n_q_heads
-    sale_ms = quant_ms + select_ms + sparse_ms
-    quant_bytes = (w.n_q_heads + w.n_kv_heads) * w.seq_len * (256 + 64) + (w.n_q_heads + w.n_kv_heads) * n_q * 4
-
-    kernels = {
-        "quantize": {"bound": "hbm", "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "ms": quant_ms},
-        "select": {"bound": "mfma", "achieved": middle_pairs * 2.0 * 64 * args.block_k * 128 / (select_ms * 1e-3) / 1e12,
-                   "peak": PEAK_FP6_TFLOPS, "unit": "TFLOP/s", "ms": select_ms},
-        "sparse_attn": {"bound": "mfma", "achieved": kept_pairs * flop_pair / (sparse_ms * 1e-3) / 1e12,
-                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "ms": sparse_ms},
-    }
-    if dense_ms:
-        kernels["dense_attn"] = {"bound": "mfma", "achieved": causal_pairs * flop_pair / (dense_ms * 1e-3) / 1e12,
-                                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "ms": dense_ms}
-    for kv in kernels.values():
-        kv["frac"] = kv["achieved"] / kv["peak"]
+    fig, (q, k, v) = measure(w, args.steps, args.warmup, args.dense_steps)
+    kernels = fig["kernels"]
     dominant = max(("quantize", "select", "sparse_attn"), key=lambda n: kernels[n]["ms"])
     roof = dict(kernels[dominant])
     roof.pop("ms")
@@ -185,39 +222,46 @@ def main() -> int:
             roof["traffic"] = {"read_bytes": t["fetch_bytes"], "write_bytes": t["write_bytes"],
                                "source": os.path.relpath(tfile, ROOT)}
 
-    if args.attn_int8_qk:       # the first product runs at the int8 MFMA rate, the second at the bf16 rate
-        for n in ("sparse_attn", "dense_attn"):
-            if n in kernels:
-                kernels[n]["peak"] = 2.0 / (1.0 / PEAK_BF16_TFLOPS + 1.0 / PEAK_INT8_TOPS)
-                kernels[n]["frac"] = kernels[n]["achieved"] / kernels[n]["peak"]
-        roof = dict(kernels[dominant]); roof.pop("ms"); roof.update({"kernel": dominant, "traffic": None})
+    # the other lengths of the metric (32K and 64K of the same layer), a few steps each
+    lengths = {}
+    if args.lengths and args.workload == "llama31-8b-layer-128k" and args.tau is None:
+        for name in ("llama31-8b-layer-32k", "llama31-8b-layer-64k"):
+            f2, _ = measure(inputs.WORKLOADS[name], 5, 2, 2)
+            lengths[name] = {key: f2[key] for key in ("sale_ms", "stages_ms", "density", "select_overhead_pct",
+                                                       "select_overhead_pct_of_dense_at_60pct_peak",
+                                                       "computation_pass_speedup", "end_to_end_speedup", "effective_tflops")}
+            lengths[name]["frac"] = {n: kv["frac"] for n, kv in f2["kernels"].items()}
+            lengths[name]["achieved"] = {n: kv["achieved"] for n, kv in f2["kernels"].items()}
+
     out = {
         "metric": "sparse prefill attn ms + speedup vs own dense kernel at 128K; select overhead %",
-        "value": sale_ms,
+        "value": fig["sale_ms"],
         "unit": "ms",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": wall_ms,
+        "ms_per_step": fig["wall_ms"],
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "seq_len": w.seq_len, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local), "attn_int8_qk": bool(args.attn_int8_qk),
-                   "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
+                   "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local),
+                   "attn_int8_qk": bool(args.attn_int8_qk), "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
                    "seed": w.seed},
-        "stages_ms": {"quantize": quant_ms, "select": select_ms, "sparse_attn": sparse_ms, "dense_attn": dense_ms},
-        "density": density,
-        "select_overhead_pct": None if not dense_ms else 100.0 * (quant_ms + select_ms) / dense_ms,
-        "computation_pass_speedup": None if not dense_ms else dense_ms / sparse_ms,
-        "end_to_end_speedup": None if not dense_ms else dense_ms / sale_ms,
-        "effective_tflops": causal_pairs * flop_pair / (sale_ms * 1e-3) / 1e12,
-        "tokens_per_s": w.seq_len / (sale_ms * 1e-3),
+        "stages_ms": fig["stages_ms"],
+        "density": fig["density"],
+        "select_overhead_pct": fig["select_overhead_pct"],
+        "select_overhead_pct_of_dense_at_60pct_peak": fig["select_overhead_pct_of_dense_at_60pct_peak"],
+        "computation_pass_speedup": fig["computation_pass_speedup"],
+        "end_to_end_speedup": fig["end_to_end_speedup"],
+        "effective_tflops": fig["effective_tflops"],
+        "tokens_per_s": fig["tokens_per_s"],
         "roofline": roof,
         "kernels": kernels,
-        "input_gen_s": t_gen,
+        "lengths": lengths,
+        "input_gen_s": fig["input_gen_s"],
     }
     if args.cpu_units > 0 and not args.attn_int8_qk:      # (the CPU leg times the unquantized oracle path)
         out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_units, block_k=args.block_k,

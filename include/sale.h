@@ -15,9 +15,18 @@
  *   the default stream), never synchronise (sale_calibrate_tau excepted) and
  *   keep no global state (sale_select_static excepted: its scratch memory is a
  *   static device array of the library).
- * - All tensors are contiguous, row-major, last dimension fastest:
- *     Q, O : bf16 [batch][n_q_heads ][seq_len][head_dim]
- *     K, V : bf16 [batch][n_kv_heads][seq_len][head_dim]
+ * - Q, K, V and O are addressed through element strides (sale_params_t):
+ *     Q, O : bf16 (batch, n_q_heads,  seq_len, head_dim)
+ *     K, V : bf16 (batch, n_kv_heads, seq_len, head_dim)
+ *   element (b, h, t, c) of X lies at  x + b * x_stride[0] + h * x_stride[1] +
+ *   t * x_stride[2] + c  (the last dimension is always contiguous), so both the
+ *   [batch][head][token][d] layout and the [batch][token][head][d] layout of a
+ *   projection output are read and written in place.  A stride triple that is
+ *   all zero means contiguous [batch][heads][seq_len][head_dim].  Strides are
+ *   non-negative multiples of 8 elements (16-byte rows), the token stride at
+ *   least head_dim; rows must not overlap.  Every OTHER tensor (codes, scales,
+ *   masks, counts, statistics, lse) is contiguous, row-major, in the layout
+ *   stated at its call.
  *   Query head h reads KV head h / (n_q_heads / n_kv_heads)  (GQA).
  * - Return value: SALE_OK (0) or a negative sale_status.  Arguments are checked
  *   before anything is launched; a failed check launches nothing.
@@ -92,6 +101,11 @@ typedef struct sale_params {
   int32_t local_blocks; /* key blocks ending at, and including, the diagonal one
                            that are always kept and feed the statistics          */
   uint32_t flags;       /* SALE_FLAG_*                                           */
+  /* element strides of (batch, head, token); all zero = contiguous [batch][heads][N][d] */
+  int64_t q_stride[3];
+  int64_t k_stride[3];
+  int64_t v_stride[3];
+  int64_t o_stride[3];
 } sale_params_t;
 
 /* Which call a workspace is for. */
@@ -115,7 +129,7 @@ const char* sale_status_string(int status);
  *   amax = max|x|; scale = amax / 7; code = clamp(rint(x * (7 / amax)), -7, 7)
  * (round half to even; an all-zero block gets scale 1 and codes 0).
  *
- *   q, k     in : bf16, layouts above
+ *   q, k     in : bf16, strided as above
  *   q4       out: uint8 [batch][n_q_heads ][N][d/2]; byte c of a row holds channel
  *                 2c in bits 0..3 and channel 2c+1 in bits 4..7 (two's complement)
  *   k4       out: uint8 [batch][n_kv_heads][N][d/2], same packing
@@ -189,7 +203,7 @@ int sale_select_static(const sale_params_t* p, const void* q, const void* k,
  *   block_mask in : layout of sale_select
  *   row_counts in : optional (may be NULL) per-row kept-block counts, used only
  *                   to order work
- *   o          out: bf16, layout of Q
+ *   o          out: bf16, strided by o_stride
  *   lse        out: optional (may be NULL) fp32 [batch][n_q_heads][N], natural-log
  *                   sum-exp of the kept logits S[r,c] = q_r . k_c / sqrt(d) of each row
  *                   (Sec. 3.1).  Accuracy: within 5e-3 absolute of the exact value.

@@ -16,6 +16,17 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
     if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
     if (p->seq_len / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
   }
+  // strides: all zero (contiguous) or non-negative multiples of 8 elements with whole rows apart
+  const int64_t* triples[4] = {p->q_stride, p->k_stride, p->v_stride, p->o_stride};
+  const int heads_of[4] = {p->n_q_heads, p->n_kv_heads, p->n_kv_heads, p->n_q_heads};
+  for (int x = 0; x < 4; ++x) {
+    const int64_t* st = triples[x];
+    if (st[0] == 0 && st[1] == 0 && st[2] == 0) continue;
+    for (int e = 0; e < 3; ++e)
+      if (st[e] < 0 || (st[e] & 7)) return SALE_ERR_BAD_SHAPE;
+    if (st[2] < p->head_dim) return SALE_ERR_BAD_SHAPE;
+    if ((heads_of[x] > 1 && st[1] == 0) || (p->batch > 1 && st[0] == 0)) return SALE_ERR_BAD_SHAPE;
+  }
   // 32-bit index guards used by the kernels
   if ((long)p->batch * p->n_q_heads * (long)(p->seq_len / 32) > 0x7FFFFFFFL) return SALE_ERR_UNSUPPORTED;
   return SALE_OK;
@@ -36,6 +47,20 @@ Geo make_geo(const sale_params_t* p) {
   g.local_blocks = p->local_blocks;
   g.seg = (p->flags & SALE_FLAG_SEGMENT_LOCAL) ? kSegmentBlocks : 0;
   g.stats_causal = (p->flags & SALE_FLAG_STATS_CAUSAL) ? 1 : 0;
+  auto layout = [&](const int64_t* st, int heads) {
+    Strided s;
+    s.heads = heads;
+    if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
+      s.st = kHeadDim; s.sh = (long long)p->seq_len * kHeadDim; s.sb = s.sh * heads;
+    } else {
+      s.sb = st[0]; s.sh = st[1]; s.st = st[2];
+    }
+    return s;
+  };
+  g.sq = layout(p->q_stride, p->n_q_heads);
+  g.sk = layout(p->k_stride, p->n_kv_heads);
+  g.sv = layout(p->v_stride, p->n_kv_heads);
+  g.so = layout(p->o_stride, p->n_q_heads);
   return g;
 }
 

@@ -59,19 +59,20 @@ namespace sale {
 // (the key order inside V' is the order in which the S^T accumulator registers
 // hand P^T to the second product).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16_t* __restrict__ k,
-                                                           const uint16_t* __restrict__ v, u32x4* __restrict__ kp,
-                                                           u32x4* __restrict__ vp) {
+__global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16_t* __restrict__ k, Strided lk,
+                                                           const uint16_t* __restrict__ v, Strided lv,
+                                                           u32x4* __restrict__ kp, u32x4* __restrict__ vp) {
   __shared__ uint16_t sv[64 * (kHeadDim + 2)];
   const int tid = threadIdx.x;
   const size_t tile = blockIdx.x;                      // flattened (kv head, block j): rows tile*64 .. +63
-  const uint16_t* kt = k + tile * 64 * kHeadDim;
-  const uint16_t* vt = v + tile * 64 * kHeadDim;
+  const int tiles_per_head = seq / 64;
+  const uint16_t* kt = k + row_off(lk, (int)(tile / tiles_per_head), (int)(tile % tiles_per_head) * 64);
+  const uint16_t* vt = v + row_off(lv, (int)(tile / tiles_per_head), (int)(tile % tiles_per_head) * 64);
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int chunk = tid + 256 * r;                   // V tile -> LDS, rows padded by one bank
     const int row = chunk >> 4, col = (chunk & 15) * 8;
-    const u32x4 w = *(const u32x4*)(vt + row * kHeadDim + col);
+    const u32x4 w = *(const u32x4*)(vt + (size_t)row * lv.st + col);
     uint32_t* d = (uint32_t*)&sv[row * (kHeadDim + 2) + col];
     d[0] = w[0]; d[1] = w[1]; d[2] = w[2]; d[3] = w[3];
   }
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16
   for (int r = 0; r < 4; ++r) {
     const int oc = tid + 256 * r;
     const int lane = oc & 63, s = (oc >> 6) & 7, mt = oc >> 9;
-    kp[tile * 1024 + oc] = *(const u32x4*)(kt + (32 * mt + (lane & 31)) * kHeadDim + 16 * s + 8 * (lane >> 5));
+    kp[tile * 1024 + oc] = *(const u32x4*)(kt + (size_t)(32 * mt + (lane & 31)) * lk.st + 16 * s + 8 * (lane >> 5));
   }
   __syncthreads();
 #pragma unroll
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
       for (int s = 0; s < 4; ++s) qf8[nt][s] = *(const i32x4*)(row + 32 * s);
     } else {
-      const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+      const uint16_t* row = q + row_off(g.sq, u.qh, u.i * 64 + 32 * nt + c) + 8 * h;
 #pragma unroll
       for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
     }
@@ -553,7 +554,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
       if constexpr (QK8) {
         // The 8-bit logits are those of K minus its mean key, i.e. Eq. 1's logits of this row minus q_r . mean /
         // sqrt(d) (which the softmax cancels in O); lse is reported for Eq. 1's S, so the shift goes back in.
-        const uint16_t* qr = q + row * kHeadDim;
+        const uint16_t* qr = q + row_off(g.sq, u.qh, u.i * 64 + 32 * nt + c);
         const float* mean = q8o.k_mean + (size_t)u.kvh * kHeadDim;
         float dot = 0.0f;
         for (int ch = 0; ch < kHeadDim; ++ch) dot = __builtin_fmaf(bf16_bits_to_float(qr[ch]), mean[ch], dot);
@@ -564,11 +565,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   }
   if (!o32) {
     // (each wave reads back only its own tile: no barrier, LDS operations of a wave complete in order)
-    uint16_t* const out = o + ((size_t)u.qh * g.seq + u.i * 64) * kHeadDim;
+    uint16_t* const out = o + row_off(g.so, u.qh, u.i * 64);
 #pragma unroll
     for (int it = 0; it < 16; ++it) {
       const int r = 4 * it + (lane >> 4), ch = 8 * (lane & 15);
-      *(u32x4*)(out + r * kHeadDim + ch) = *(const u32x4*)(tile + r * kRowPad + ch);
+      *(u32x4*)(out + (size_t)r * g.so.st + ch) = *(const u32x4*)(tile + r * kRowPad + ch);
     }
   }
 }
@@ -844,8 +845,8 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   float* st_ml = (float*)(st_o + n_units * 2048);
   int32_t* order = (int32_t*)(st_ml + n_units * 256);
   int32_t* assign = order + n_units;
-  rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k,
-                                                                                    (const uint16_t*)v, kp, vp);
+  rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k, g.sk,
+                                                                                    (const uint16_t*)v, g.sv, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const bool qk8 = (p->flags & SALE_FLAG_ATTN_INT8_QK) != 0;
   Qk8 q8o = {nullptr, nullptr, nullptr, nullptr, nullptr};

@@ -9,23 +9,27 @@
 namespace sale {
 
 template <int ROWS>
-__global__ __launch_bounds__(256) void quantize_kernel(const u32x4* __restrict__ xa, uint32_t* __restrict__ ca,
-                                                       float* __restrict__ sa, int n_blocks_a,
-                                                       const u32x4* __restrict__ xb, uint32_t* __restrict__ cb,
-                                                       float* __restrict__ sb) {
+__global__ __launch_bounds__(256) void quantize_kernel(int seq, const uint16_t* __restrict__ xa, Strided la,
+                                                       uint32_t* __restrict__ ca, float* __restrict__ sa, int n_blocks_a,
+                                                       const uint16_t* __restrict__ xb, Strided lb,
+                                                       uint32_t* __restrict__ cb, float* __restrict__ sb) {
   constexpr int CH = ROWS * 16 / 256;   // 16-byte chunks per thread
   __shared__ float wave_max[4];
   int blk = blockIdx.x;
-  const u32x4* x = xa;
+  const uint16_t* x = xa;
+  Strided lay = la;
   uint32_t* codes = ca;
   float* scale = sa;
-  if (blk >= n_blocks_a) { blk -= n_blocks_a; x = xb; codes = cb; scale = sb; }
-  const size_t base = (size_t)blk * (ROWS * 16);
+  if (blk >= n_blocks_a) { blk -= n_blocks_a; x = xb; lay = lb; codes = cb; scale = sb; }
+  const size_t base = (size_t)blk * (ROWS * 16);      // 16-byte chunk (input) / dword (codes) index of the block
   const int t = threadIdx.x;
+  // block blk = rows (blk % bph) * ROWS .. of flat head blk / bph; chunk t + 256 i = row (t / 16 + 16 i), chunk t % 16
+  const int bph = seq / ROWS;
+  const uint16_t* first = x + row_off(lay, blk / bph, (blk % bph) * ROWS + (t >> 4)) + 8 * (t & 15);
 
   u32x4 raw[CH];
 #pragma unroll
-  for (int i = 0; i < CH; ++i) raw[i] = __builtin_nontemporal_load(&x[base + t + 256 * i]);
+  for (int i = 0; i < CH; ++i) raw[i] = __builtin_nontemporal_load((const u32x4*)(first + (size_t)(16 * i) * lay.st));
 
   float v[CH][8];
   float amax = 0.0f;
@@ -63,12 +67,12 @@ __global__ __launch_bounds__(256) void quantize_kernel(const u32x4* __restrict__
 }
 
 template <int ROWS>
-static int launch_quant(const void* xa, uint8_t* ca, float* sa, long blocks_a, const void* xb, uint8_t* cb, float* sb,
-                        long blocks_b, hipStream_t st) {
+static int launch_quant(int seq, const void* xa, const Strided& la, uint8_t* ca, float* sa, long blocks_a, const void* xb,
+                        const Strided& lb, uint8_t* cb, float* sb, long blocks_b, hipStream_t st) {
   long total = blocks_a + blocks_b;
   if (total == 0) return SALE_OK;
-  quantize_kernel<ROWS><<<dim3((unsigned)total), dim3(256), 0, st>>>((const u32x4*)xa, (uint32_t*)ca, sa, (int)blocks_a,
-                                                                    (const u32x4*)xb, (uint32_t*)cb, sb);
+  quantize_kernel<ROWS><<<dim3((unsigned)total), dim3(256), 0, st>>>(seq, (const uint16_t*)xa, la, (uint32_t*)ca, sa,
+                                                                    (int)blocks_a, (const uint16_t*)xb, lb, (uint32_t*)cb, sb);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }
 
@@ -82,15 +86,17 @@ extern "C" int sale_quantize_qk(const sale_params_t* p, const void* q, const voi
   int rc = validate_common(p, kGeomQuantize);
   if (rc != SALE_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
+  const Geo g = make_geo(p);
+  const int n = p->seq_len;
   const long rows_q = (long)p->batch * p->n_q_heads * p->seq_len;
   const long rows_k = (long)p->batch * p->n_kv_heads * p->seq_len;
   if (p->block_q == p->block_k) {
-    return p->block_q == 64 ? launch_quant<64>(q, q4, q_scale, rows_q / 64, k, k4, k_scale, rows_k / 64, st)
-                            : launch_quant<32>(q, q4, q_scale, rows_q / 32, k, k4, k_scale, rows_k / 32, st);
+    return p->block_q == 64 ? launch_quant<64>(n, q, g.sq, q4, q_scale, rows_q / 64, k, g.sk, k4, k_scale, rows_k / 64, st)
+                            : launch_quant<32>(n, q, g.sq, q4, q_scale, rows_q / 32, k, g.sk, k4, k_scale, rows_k / 32, st);
   }
-  rc = p->block_q == 64 ? launch_quant<64>(q, q4, q_scale, rows_q / 64, nullptr, nullptr, nullptr, 0, st)
-                        : launch_quant<32>(q, q4, q_scale, rows_q / 32, nullptr, nullptr, nullptr, 0, st);
+  rc = p->block_q == 64 ? launch_quant<64>(n, q, g.sq, q4, q_scale, rows_q / 64, nullptr, g.sq, nullptr, nullptr, 0, st)
+                        : launch_quant<32>(n, q, g.sq, q4, q_scale, rows_q / 32, nullptr, g.sq, nullptr, nullptr, 0, st);
   if (rc != SALE_OK) return rc;
-  return p->block_k == 64 ? launch_quant<64>(k, k4, k_scale, rows_k / 64, nullptr, nullptr, nullptr, 0, st)
-                          : launch_quant<32>(k, k4, k_scale, rows_k / 32, nullptr, nullptr, nullptr, 0, st);
+  return p->block_k == 64 ? launch_quant<64>(n, k, g.sk, k4, k_scale, rows_k / 64, nullptr, g.sk, nullptr, nullptr, 0, st)
+                          : launch_quant<32>(n, k, g.sk, k4, k_scale, rows_k / 32, nullptr, g.sk, nullptr, nullptr, 0, st);
 }

@@ -10,13 +10,14 @@ namespace sale {
 
 // Exact column sums: bf16 values summed in fp64 lose nothing for any realistic value range, so the result
 // does not depend on the order of the additions.  One workgroup per (KV head, 64-row tile): partial[c].
-__global__ __launch_bounds__(256) void ksum_kernel(const uint16_t* __restrict__ k, double* __restrict__ partial) {
+__global__ __launch_bounds__(256) void ksum_kernel(const uint16_t* __restrict__ k, Strided lk, int tiles_per_head,
+                                                   double* __restrict__ partial) {
   __shared__ double other[128];
   const int c = threadIdx.x & 127, phase = threadIdx.x >> 7;
-  const uint16_t* rows = k + ((size_t)blockIdx.x * 64 + phase * 32) * kHeadDim + c;
+  const uint16_t* rows = k + row_off(lk, blockIdx.x / tiles_per_head, (blockIdx.x % tiles_per_head) * 64 + phase * 32) + c;
   double s = 0.0;
 #pragma unroll 8
-  for (int r = 0; r < 32; ++r) s += (double)bf16_bits_to_float(rows[r * kHeadDim]);
+  for (int r = 0; r < 32; ++r) s += (double)bf16_bits_to_float(rows[(size_t)r * lk.st]);
   if (phase == 1) other[c] = s;
   __syncthreads();
   if (phase == 0) partial[(size_t)blockIdx.x * 128 + c] = s + other[c];
@@ -37,13 +38,13 @@ __global__ __launch_bounds__(128) void kmean_kernel(const double* __restrict__ p
 //   [head][tile][mt 0..1][ks 0..3][lane 0..63] 16 bytes: channels 32ks + 16(lane/32) .. of key row 32mt + lane%32;
 // otherwise row-major [head][row][128 bytes].
 template <bool FRAG>
-__global__ __launch_bounds__(256) void quantize8_kernel(const uint16_t* __restrict__ x, const float* __restrict__ mean,
-                                                        int tiles_per_head, int8_t* __restrict__ codes,
-                                                        float* __restrict__ scale) {
+__global__ __launch_bounds__(256) void quantize8_kernel(const uint16_t* __restrict__ x, Strided lx,
+                                                        const float* __restrict__ mean, int tiles_per_head,
+                                                        int8_t* __restrict__ codes, float* __restrict__ scale) {
   __shared__ float wave_max[4];
   const int t = threadIdx.x, r = t >> 2, cq = t & 3;
   const size_t blk = blockIdx.x;
-  const u32x4* src = (const u32x4*)(x + (blk * 64 + r) * kHeadDim + 32 * cq);
+  const u32x4* src = (const u32x4*)(x + row_off(lx, (int)(blk / tiles_per_head), (int)(blk % tiles_per_head) * 64 + r) + 32 * cq);
   float v[32];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -122,18 +123,19 @@ Int8Operands carve_int8_operands(const sale_params_t* p, void* base) {
 int launch_int8_operands(const sale_params_t* p, const void* q, const void* k, const Int8Operands& w, bool frag_k,
                          hipStream_t st) {
   const int n_kvh = p->batch * p->n_kv_heads, n_qh = p->batch * p->n_q_heads, tiles = p->seq_len / 64;
-  ksum_kernel<<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, w.partial);
+  const Geo g = make_geo(p);
+  ksum_kernel<<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, g.sk, tiles, w.partial);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   kmean_kernel<<<dim3((unsigned)n_kvh), dim3(128), 0, st>>>(w.partial, tiles, p->seq_len, w.k_mean);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  quantize8_kernel<false><<<dim3((unsigned)(n_qh * tiles)), dim3(256), 0, st>>>((const uint16_t*)q, nullptr, tiles, w.q8,
-                                                                               w.q_scale);
+  quantize8_kernel<false><<<dim3((unsigned)(n_qh * tiles)), dim3(256), 0, st>>>((const uint16_t*)q, g.sq, nullptr, tiles,
+                                                                               w.q8, w.q_scale);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   if (frag_k)
-    quantize8_kernel<true><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, w.k_mean, tiles, w.k8,
-                                                                                 w.k_scale);
+    quantize8_kernel<true><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, g.sk, w.k_mean, tiles,
+                                                                                 w.k8, w.k_scale);
   else
-    quantize8_kernel<false><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, w.k_mean, tiles,
+    quantize8_kernel<false><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, g.sk, w.k_mean, tiles,
                                                                                   w.k8, w.k_scale);
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
 }

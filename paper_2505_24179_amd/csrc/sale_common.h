@@ -28,6 +28,17 @@ constexpr int kSegmentBlocks = 4;            // key blocks per segment (Appendix
 constexpr int kMaskWordsMax = 64;            // longest mask row, in 64-bit words
 constexpr int kMaxSeqLen = kMaskWordsMax * 64 * kBlockK;   // 262144 tokens (131072 with b_k = 32)
 
+// How one of Q, K, V, O is laid out: element (flat head f = b * heads + h, token t, channel c) lies at
+// (f / heads) * sb + (f % heads) * sh + t * st + c.
+struct Strided {
+  long long sb, sh, st;
+  int heads;
+};
+__host__ __device__ __forceinline__ size_t row_off(const Strided& s, int flat_head, int token) {
+  return (size_t)(flat_head / s.heads) * (size_t)s.sb + (size_t)(flat_head % s.heads) * (size_t)s.sh +
+         (size_t)token * (size_t)s.st;
+}
+
 // Flattened geometry handed to kernels.
 struct Geo {
   int n_qh;        // batch * n_q_heads
@@ -43,6 +54,7 @@ struct Geo {
   int local_blocks;
   int seg;         // segment size in key blocks (0 = no segment rule for the local area)
   int stats_causal;
+  Strided sq, sk, sv, so;   // layouts of Q, K, V, O
 };
 
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {

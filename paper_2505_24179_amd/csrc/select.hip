@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
   bf16x8 qf[2][8];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
-    const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+    const uint16_t* row = q + row_off(g.sq, u.qh, u.i * 64 + 32 * nt + c) + 8 * h;
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
   }
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
         for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const uint16_t* row = k + ((size_t)u.kvh * g.seq + j * g.bk + 32 * mt + c) * kHeadDim + 8 * h;
+      const uint16_t* row = k + row_off(g.sk, u.kvh, j * g.bk + 32 * mt + c) + 8 * h;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
         const bf16x8 a = *(const bf16x8*)(row + 16 * s);
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __
   bf16x8 qf[2][8];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
-    const uint16_t* row = q + ((size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c) * kHeadDim + 8 * h;
+    const uint16_t* row = q + row_off(g.sq, u.qh, u.i * 64 + 32 * nt + c) + 8 * h;
 #pragma unroll
     for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
   }
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __
           for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const uint16_t* row = k + ((size_t)u.kvh * g.seq + j * g.bk + 32 * mt + c) * kHeadDim + 8 * h;
+        const uint16_t* row = k + row_off(g.sk, u.kvh, j * g.bk + 32 * mt + c) + 8 * h;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
           const bf16x8 a = *(const bf16x8*)(row + 16 * s);

@@ -34,7 +34,8 @@ WS_INT8_OPERANDS = 5
 class _Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "seq_len", "head_dim",
-        "block_q", "block_k", "sink_blocks", "local_blocks")] + [("flags", ctypes.c_uint32)]
+        "block_q", "block_k", "sink_blocks", "local_blocks")] + [("flags", ctypes.c_uint32)] + \
+        [(n, ctypes.c_int64 * 3) for n in ("q_stride", "k_stride", "v_stride", "o_stride")]
 
 
 @dataclass(frozen=True)
@@ -50,9 +51,16 @@ class Params:
     local_blocks: int = 4
     flags: int = 0
 
-    def c(self) -> _Params:
-        return _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.seq_len, self.head_dim,
-                       self.block_q, self.block_k, self.sink_blocks, self.local_blocks, self.flags)
+    def c(self, q=None, k=None, v=None, o=None) -> _Params:
+        """The C struct.  Strides of Q, K, V, O are taken from the tensors given: zero (= contiguous) for a
+        contiguous tensor, otherwise its (batch, head, token) element strides, e.g. for a [B, N, H, d]
+        projection output viewed as [B, H, N, d] with .transpose(1, 2)."""
+        cp = _Params(self.batch, self.n_q_heads, self.n_kv_heads, self.seq_len, self.head_dim,
+                     self.block_q, self.block_k, self.sink_blocks, self.local_blocks, self.flags)
+        for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
+            if t is not None and not t.is_contiguous():
+                getattr(cp, name)[:] = [int(x) for x in t.stride()[:3]]
+        return cp
 
     @property
     def n_q(self) -> int:
@@ -124,6 +132,24 @@ def _expect(name: str, t, dtype, numel: int, optional: bool = False):
         raise ValueError(f"{name}: expected {numel} elements for these parameters, got {t.numel()} (shape {tuple(t.shape)})")
 
 
+def _expect_bhnd(name: str, t, p: "Params", heads: int):
+    """Q, K, V or O: a bf16 device tensor, either contiguous with batch * heads * seq_len * head_dim elements or
+    a strided view of shape [batch, heads, seq_len, head_dim] whose last dimension is contiguous (its other
+    three strides then go into the C struct: non-negative multiples of 8 elements)."""
+    if t is not None and t.is_cuda and not t.is_contiguous():
+        want = (p.batch, heads, p.seq_len, p.head_dim)
+        if t.dtype != torch.bfloat16:
+            raise ValueError(f"{name}: expected dtype torch.bfloat16, got {t.dtype}")
+        if tuple(t.shape) != want:
+            raise ValueError(f"{name}: a strided tensor must have shape {want}, got {tuple(t.shape)}")
+        st = t.stride()
+        if st[3] != 1 or any(x < 0 or x % 8 for x in st[:3]) or st[2] < p.head_dim:
+            raise ValueError(f"{name}: strides {st} are not supported (last dimension contiguous, the others "
+                             "non-negative multiples of 8 elements, rows at least head_dim apart)")
+        return
+    _expect(name, t, torch.bfloat16, p.batch * heads * p.seq_len * p.head_dim)
+
+
 def _expect_ws(ws, need: int):
     """-> the workspace's size in BYTES (whatever its dtype).  Size and alignment are the library's to judge
     (SALE_ERR_WORKSPACE)."""
@@ -164,11 +190,11 @@ def quantize_qk(p: Params, q: torch.Tensor, k: torch.Tensor, out=None):
     else:
         q4, k4, qs, ks = out
     nq, nk = _qkv_numel(p)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads)
     _expect("q4", q4, torch.uint8, nq // 2); _expect("k4", k4, torch.uint8, nk // 2)
     _expect("q_scale", qs, torch.float32, p.batch * p.n_q_heads * (p.seq_len // p.block_q))
     _expect("k_scale", ks, torch.float32, p.batch * p.n_kv_heads * (p.seq_len // p.block_k))
-    _check(_lib.sale_quantize_qk(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(qs), _ptr(ks), _stream()))
+    _check(_lib.sale_quantize_qk(ctypes.byref(p.c(q, k)), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(qs), _ptr(ks), _stream()))
     return q4, k4, qs, ks
 
 
@@ -189,7 +215,7 @@ def select(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, want_st
         ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
     nq, nk = _qkv_numel(p)
     est16 = bool(p.flags & FLAG_SELECT_16BIT)          # the 16-bit estimate does not read the codes
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads)
     _expect("q4", q4, torch.uint8, nq // 2, optional=est16); _expect("k4", k4, torch.uint8, nk // 2, optional=est16)
     _expect("q_scale", q_scale, torch.float32, p.batch * p.n_q_heads * p.n_q, optional=est16)
     _expect("k_scale", k_scale, torch.float32, p.batch * p.n_kv_heads * p.n_k, optional=est16)
@@ -198,7 +224,7 @@ def select(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, want_st
     _expect("tau", tau, torch.float32, tau.numel())
     _expect("block_mask", mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
     _expect("row_counts", counts, torch.int32, p.batch * p.n_q_heads * p.n_q)
-    _check(_lib.sale_select(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
+    _check(_lib.sale_select(ctypes.byref(p.c(q, k)), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
                             _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), _ptr(m), _ptr(l),
                             _ptr(ws), _expect_ws(ws, need), _stream()))
     return mask, counts, m, l
@@ -213,14 +239,14 @@ def select_static(p: Params, q, k, q4, k4, q_scale, k_scale, tau: torch.Tensor, 
     mask, counts = out
     nq, nk = _qkv_numel(p)
     est16 = bool(p.flags & FLAG_SELECT_16BIT)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads)
     _expect("q4", q4, torch.uint8, nq // 2, optional=est16); _expect("k4", k4, torch.uint8, nk // 2, optional=est16)
     _expect("q_scale", q_scale, torch.float32, p.batch * p.n_q_heads * p.n_q, optional=est16)
     _expect("k_scale", k_scale, torch.float32, p.batch * p.n_kv_heads * p.n_k, optional=est16)
     _expect("tau", tau, torch.float32, tau.numel())
     _expect("block_mask", mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
     _expect("row_counts", counts, torch.int32, p.batch * p.n_q_heads * p.n_q)
-    _check(_lib.sale_select_static(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
+    _check(_lib.sale_select_static(ctypes.byref(p.c(q, k)), _ptr(q), _ptr(k), _ptr(q4), _ptr(k4), _ptr(q_scale), _ptr(k_scale),
                                    _ptr(tau), tau.numel(), _ptr(mask), _ptr(counts), None, None, _stream()))
     return mask, counts
 
@@ -232,11 +258,11 @@ def sparse_attn(p: Params, q, k, v, block_mask, row_counts=None, want_lse: bool 
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_SPARSE_ATTN)), dtype=torch.uint8, device=q.device)
     nq, nk = _qkv_numel(p)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
-    _expect("o", o, torch.bfloat16, nq)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads); _expect_bhnd("v", v, p, p.n_kv_heads)
+    _expect_bhnd("o", o, p, p.n_q_heads)
     _expect("block_mask", block_mask, (torch.int64, torch.uint64), p.batch * p.n_q_heads * p.n_q * p.words)
     _expect("row_counts", row_counts, torch.int32, p.batch * p.n_q_heads * p.n_q, optional=True)
-    _check(_lib.sale_sparse_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(block_mask), _ptr(row_counts),
+    _check(_lib.sale_sparse_attn(ctypes.byref(p.c(q, k, v, o)), _ptr(q), _ptr(k), _ptr(v), _ptr(block_mask), _ptr(row_counts),
                                  _ptr(o), _ptr(lse), _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_SPARSE_ATTN)), _stream()))
     return o, lse
 
@@ -248,9 +274,9 @@ def dense_attn(p: Params, q, k, v, want_lse: bool = False, out=None, ws=None):
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_DENSE_ATTN)), dtype=torch.uint8, device=q.device)
     nq, nk = _qkv_numel(p)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
-    _expect("o", o, torch.bfloat16, nq)
-    _check(_lib.sale_dense_attn(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads); _expect_bhnd("v", v, p, p.n_kv_heads)
+    _expect_bhnd("o", o, p, p.n_q_heads)
+    _check(_lib.sale_dense_attn(ctypes.byref(p.c(q, k, v, o)), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
                                 _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_DENSE_ATTN)), _stream()))
     return o, lse
 
@@ -270,14 +296,14 @@ def attn_int8_operands(p: Params, q, k):
     k_mean f32 [B,Hkv,d]): the 8-bit operands of the quantized Computation-Pass (parity hook)."""
     dev = q.device
     nq, nk = _qkv_numel(p)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads)
     q8 = torch.empty(p.batch, p.n_q_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
     k8 = torch.empty(p.batch, p.n_kv_heads, p.seq_len, p.head_dim, dtype=torch.int8, device=dev)
     qs = torch.empty(p.batch, p.n_q_heads, p.seq_len // 64, dtype=torch.float32, device=dev)
     ks = torch.empty(p.batch, p.n_kv_heads, p.seq_len // 64, dtype=torch.float32, device=dev)
     mean = torch.empty(p.batch, p.n_kv_heads, p.head_dim, dtype=torch.float32, device=dev)
     ws = torch.empty(max(1, workspace_bytes(p, WS_INT8_OPERANDS)), dtype=torch.uint8, device=dev)
-    _check(_lib.sale_attn_int8_operands(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(q8), _ptr(k8), _ptr(qs), _ptr(ks),
+    _check(_lib.sale_attn_int8_operands(ctypes.byref(p.c(q, k)), _ptr(q), _ptr(k), _ptr(q8), _ptr(k8), _ptr(qs), _ptr(ks),
                                         _ptr(mean), _ptr(ws), ws.numel(), _stream()))
     return q8, k8, qs, ks, mean
 
@@ -286,13 +312,13 @@ def calibrate_tau(p: Params, q, k, v, tau0: float = 0.008, theta: float = 0.4, m
     """-> (tau f32 [Hq], err f32 [Hq], halvings i32 [Hq]); synchronises the current stream."""
     dev = q.device
     nq, nk = _qkv_numel(p)
-    _expect("q", q, torch.bfloat16, nq); _expect("k", k, torch.bfloat16, nk); _expect("v", v, torch.bfloat16, nk)
+    _expect_bhnd("q", q, p, p.n_q_heads); _expect_bhnd("k", k, p, p.n_kv_heads); _expect_bhnd("v", v, p, p.n_kv_heads)
     tau = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
     err = torch.empty(p.n_q_heads, dtype=torch.float32, device=dev)
     halv = torch.empty(p.n_q_heads, dtype=torch.int32, device=dev)
     if ws is None:
         ws = torch.empty(max(1, workspace_bytes(p, WS_CALIBRATE)), dtype=torch.uint8, device=dev)
-    _check(_lib.sale_calibrate_tau(ctypes.byref(p.c()), _ptr(q), _ptr(k), _ptr(v), tau0, theta, max_halvings,
+    _check(_lib.sale_calibrate_tau(ctypes.byref(p.c(q, k, v)), _ptr(q), _ptr(k), _ptr(v), tau0, theta, max_halvings,
                                    _ptr(tau), _ptr(err), _ptr(halv), _ptr(ws), _expect_ws(ws, workspace_bytes(p, WS_CALIBRATE)),
                                    _stream()))
     return tau, err, halv

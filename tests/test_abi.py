@@ -152,3 +152,29 @@ def test_static_scratch_select_checks_before_touching_the_gpu(sale):
     assert lib.sale_select_static(ctypes.byref(fits.c()), f, f, f, f, f, f, f, 5, f, f, None, None, None) == -2
     bad = sale.Params(1, 32, 8, 16384, block_q=32)
     assert lib.sale_select_static(ctypes.byref(bad.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None) == -3
+
+
+def test_strides_are_validated(sale):
+    """Strides are element counts of (batch, head, token): all zero = contiguous; otherwise non-negative multiples
+    of 8 with rows at least head_dim apart and a head / batch stride wherever there is more than one."""
+    import ctypes
+    lib = sale.raw()
+    f = ctypes.c_void_p(0x1000)        # never dereferenced
+    good = sale.Params(2, 4, 2, 256)
+
+    def call(**strides):
+        cp = good.c()
+        for name, val in strides.items():
+            getattr(cp, name)[:] = val
+        return lib.sale_dense_attn(ctypes.byref(cp), f, f, f, f, None, f, 16, None)
+
+    assert call() == -4                                                  # valid geometry: fails on the tiny workspace only
+    assert call(q_stride=[4 * 256 * 128, 128, 4 * 128]) == -4            # [B][N][H][d]
+    assert call(o_stride=[4 * 256 * 160, 256 * 160, 160]) == -4          # padded rows
+    assert call(q_stride=[4 * 256 * 128, 128, 4 * 128 + 4]) == -2        # not a multiple of 8 elements
+    assert call(k_stride=[2 * 256 * 128, 256 * 128, 64]) == -2           # rows closer than head_dim
+    assert call(v_stride=[2 * 256 * 128, 0, 128]) == -2                  # two KV heads on top of each other
+    assert call(q_stride=[0, 256 * 128, 128]) == -2                      # two batch entries on top of each other
+    assert call(q_stride=[-8, 256 * 128, 128]) == -2
+    # the struct grew at the end: a caller that fills only the leading fields gets contiguous tensors
+    assert ctypes.sizeof(good.c()) == 40 + 4 * 3 * 8
