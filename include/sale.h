@@ -106,6 +106,17 @@ typedef struct sale_params {
   int64_t k_stride[3];
   int64_t v_stride[3];
   int64_t o_stride[3];
+  /* Variable-length batch (optional; n_seqs = 0: every batch entry is one sequence of seq_len tokens).
+   * n_seqs > 0 packs n_seqs sequences of different lengths one after the other along the token axis of a
+   * batch = 1 call: seq_len is then the TOTAL number of tokens and cu_seqlens, a HOST pointer read during
+   * the call, holds n_seqs + 1 ascending token offsets, cu_seqlens[0] = 0, cu_seqlens[n_seqs] = seq_len.
+   * Every sequence length is a positive multiple of 64 (pad shorter ones as for a single sequence) and at
+   * most 4096 key blocks.  Attention, statistics and selection never cross a sequence boundary: key block j
+   * of a mask row is the j-th block OF THAT ROW'S SEQUENCE, and the mask has ceil(longest / (64 b_k)) words
+   * per row.  Per-token and per-block tensors (codes, scales, counts, statistics, lse) are indexed by the
+   * packed position.  Not combined with SALE_FLAG_ATTN_INT8_QK or sale_calibrate_tau (SALE_ERR_UNSUPPORTED). */
+  int32_t n_seqs;
+  const int32_t* cu_seqlens;
 } sale_params_t;
 
 /* Which call a workspace is for. */
@@ -155,7 +166,8 @@ int sale_quantize_qk(const sale_params_t* p, const void* q, const void* k,
  *
  *   tau         in : fp32, DEVICE pointer, tau_len = 1 (shared) or n_q_heads
  *   block_mask  out: uint64 [batch][n_q_heads][N_q][ceil(N_k/64)]; bit (j mod 64)
- *                    of word j/64 is M_bs[i][j]
+ *                    of word j/64 is M_bs[i][j]  (variable-length batches: N_k of
+ *                    the longest sequence, j counted inside the row's sequence)
  *   row_counts  out: int32 [batch][n_q_heads][N_q], number of kept blocks per row
  *   m_out,l_out out: optional (may be NULL) fp32 [batch][n_q_heads][N]: m~, l~
  *   ws             : workspace of sale_workspace_bytes(p, SALE_WS_SELECT) bytes

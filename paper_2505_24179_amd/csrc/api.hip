@@ -12,9 +12,21 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
   if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
   if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL | SALE_FLAG_ATTN_INT8_QK)) return SALE_ERR_UNSUPPORTED;
   if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
+  if (p->n_seqs < 0 || (p->n_seqs > 0 && !p->cu_seqlens)) return SALE_ERR_BAD_SHAPE;
+  int longest = p->seq_len;
+  if (p->n_seqs > 0) {
+    if (p->batch != 1 || p->cu_seqlens[0] != 0 || p->cu_seqlens[p->n_seqs] != p->seq_len) return SALE_ERR_BAD_SHAPE;
+    longest = 0;
+    for (int s = 0; s < p->n_seqs; ++s) {
+      const int len = p->cu_seqlens[s + 1] - p->cu_seqlens[s];
+      if (len <= 0 || len % 64 != 0) return SALE_ERR_BAD_SHAPE;
+      longest = len > longest ? len : longest;
+    }
+    if (p->flags & SALE_FLAG_ATTN_INT8_QK) return SALE_ERR_UNSUPPORTED;
+  }
   if (cls != kGeomQuantize) {
     if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
-    if (p->seq_len / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
+    if (longest / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
   }
   // strides: all zero (contiguous) or non-negative multiples of 8 elements with whole rows apart
   const int64_t* triples[4] = {p->q_stride, p->k_stride, p->v_stride, p->o_stride};
@@ -42,7 +54,13 @@ Geo make_geo(const sale_params_t* p) {
   g.n_qb = p->seq_len / kBlockQ;
   g.bk = p->block_k;
   g.n_kb = p->seq_len / p->block_k;
-  g.words = (g.n_kb + 63) / 64;
+  int longest = p->seq_len;
+  if (p->n_seqs > 0) {
+    longest = 0;
+    for (int s = 0; s < p->n_seqs; ++s) longest = max(longest, p->cu_seqlens[s + 1] - p->cu_seqlens[s]);
+  }
+  g.words = (longest / p->block_k + 63) / 64;
+  g.seq_start = nullptr;
   g.sink_blocks = p->sink_blocks;
   g.local_blocks = p->local_blocks;
   g.seg = (p->flags & SALE_FLAG_SEGMENT_LOCAL) ? kSegmentBlocks : 0;
@@ -64,6 +82,45 @@ Geo make_geo(const sale_params_t* p) {
   return g;
 }
 
+size_t seq_table_bytes(const sale_params_t* p) {
+  return p->n_seqs > 0 ? (((size_t)(p->seq_len / kBlockQ) * sizeof(int32_t) + 15) & ~(size_t)15) : 0;
+}
+
+namespace {
+
+// Up to kSeqChunk sequences per launch travel as kernel arguments (copied at launch: no host buffer has to
+// outlive the call, nothing is staged or synchronised).
+constexpr int kSeqChunk = 255;
+struct SeqChunk {
+  int n;
+  int start_blk[kSeqChunk + 1];      // first 64-row block of every sequence of the chunk, and the end of the last
+};
+
+__global__ __launch_bounds__(256) void seq_table_kernel(SeqChunk c, int32_t* __restrict__ table) {
+  const int b = c.start_blk[0] + blockIdx.x * 256 + threadIdx.x;
+  if (b >= c.start_blk[c.n]) return;
+  int lo = 0, hi = c.n;              // the sequence s with start_blk[s] <= b < start_blk[s + 1]
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (c.start_blk[mid] <= b) lo = mid; else hi = mid;
+  }
+  table[b] = c.start_blk[lo];
+}
+
+}  // namespace
+
+int build_seq_table(const sale_params_t* p, int32_t* table, hipStream_t st) {
+  for (int s0 = 0; s0 < p->n_seqs; s0 += kSeqChunk) {
+    SeqChunk c;
+    c.n = min(kSeqChunk, p->n_seqs - s0);
+    for (int e = 0; e <= c.n; ++e) c.start_blk[e] = p->cu_seqlens[s0 + e] / kBlockQ;
+    const int blocks = c.start_blk[c.n] - c.start_blk[0];
+    seq_table_kernel<<<dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, st>>>(c, table);
+    if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  }
+  return SALE_OK;
+}
+
 }  // namespace sale
 
 using namespace sale;
@@ -74,7 +131,7 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
   switch (which_call) {
     case SALE_WS_SELECT:
       // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copies of Q~ and K~ (96 B per row)
-      return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96;
+      return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96 + seq_table_bytes(p);
     case SALE_WS_SPARSE_ATTN:
     case SALE_WS_DENSE_ATTN:
       // K and V copied once into MFMA fragment order, parked row state (fp32 O^T accumulators and
@@ -83,7 +140,7 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
       // (+ the 8-bit operand copies of the quantized Computation-Pass)
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
              (rows / kBlockQ) * ((1 + kMaskWordsMax / 2) * sizeof(int32_t) + 2048 * 16 + 256 * 4) + (128u << 10) + 16 +
-             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0);
+             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0) + seq_table_bytes(p);
     case SALE_WS_CALIBRATE:
       return calibrate_workspace_bytes(p);
     case SALE_WS_INT8_OPERANDS:

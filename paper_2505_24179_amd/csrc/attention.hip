@@ -172,7 +172,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 
   // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
   const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
-  const int j_last = BK32 ? 2 * u.i + 1 : u.i;      // last causally visible mask bit of the row
+  const SeqPos sp = seq_pos(g, u.i);                // (variable-length batches: block indices inside the row's sequence)
+  const int il = sp.il;
+  const int j_last = BK32 ? 2 * il + 1 : il;        // last causally visible mask bit of the row
   const int last_word = j_last >> 6;
   const int win_word = tail ? -1 : flt.win_word;
   if (win_word > last_word) return;
@@ -218,11 +220,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   const float* ks8 = nullptr;
   if constexpr (QK8) {
     sq_cs = q8o.q_scale[unit_flat] * cs;
-    k8t = (const i32x4*)q8o.k8p + (size_t)u.kvh * g.seq * 8 + lane;     // 512 16-byte chunks per 64 keys
-    ks8 = q8o.k_scale + (size_t)u.kvh * (g.seq / 64);
+    k8t = (const i32x4*)q8o.k8p + ((size_t)u.kvh * g.seq + (size_t)(u.i - il) * 64) * 8 + lane;     // 512 16-byte chunks per 64 keys
+    ks8 = q8o.k_scale + (size_t)u.kvh * (g.seq / 64) + (u.i - il);
   }
-  const bf16x8* kt = kp + (size_t)u.kvh * g.seq * 16 + lane;     // 1024 16-byte chunks per 64 keys
-  const bf16x8* vt = vp + (size_t)u.kvh * g.seq * 16 + lane;
+  // (the sequence's first key tile: u.i - il 64-row blocks into the KV head)
+  const bf16x8* kt = kp + ((size_t)u.kvh * g.seq + (size_t)(u.i - il) * 64) * 16 + lane;     // 1024 16-byte chunks per 64 keys
+  const bf16x8* vt = vp + ((size_t)u.kvh * g.seq + (size_t)(u.i - il) * 64) * 16 + lane;
   // Work proceeds in pairs of 32-key half-tiles held in slots 0 and 1; half-tile hb covers keys
   // 32hb .. 32hb+31 (half hb % 2 of the 64-key tile hb / 2 of K', V').  K operands of slot mt: kf[mt][s];
   // V operands of slot mt: vf[mt][dt][s2].
@@ -463,8 +466,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   };
   auto set_koff = [&](Pair pr, bool empty_b) {
     if constexpr (BK32) {
-      koff[0] = (pr.a - 2 * u.i) * 32;
-      koff[1] = empty_b ? kEmptySlot : (pr.b - 2 * u.i) * 32;
+      koff[0] = (pr.a - 2 * il) * 32;
+      koff[1] = empty_b ? kEmptySlot : (pr.b - 2 * il) * 32;
     }
   };
 
@@ -486,7 +489,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     bool has_next = next_pair(pn);
     set_koff(pc, lone_first);
     if (!has_next) {
-      if (BK32 || pc.a == 2 * u.i) block_step(pc, pc, T, T, T); else block_step(pc, pc, T, T, F);
+      if (BK32 || pc.a == 2 * il) block_step(pc, pc, T, T, T); else block_step(pc, pc, T, T, F);
     } else {
       // the list is read one pair ahead of the loads so that no control flow separates the stages
       load_k(pn.a, 0);
@@ -500,7 +503,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
         pc = pn; pn = pa; has_next = has_aft;
       }
       set_koff(pc, false);
-      if (BK32 || pc.a == 2 * u.i) block_step(pc, pc, F, T, T); else block_step(pc, pc, F, T, F);
+      if (BK32 || pc.a == 2 * il) block_step(pc, pc, F, T, T); else block_step(pc, pc, F, T, F);
     }
     pv_half(1);
   }
@@ -579,12 +582,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t* __restrict__ row_counts,
                                                            int32_t* __restrict__ order) {
   __shared__ int bin[kMaskWordsMax * 64 + 2];
-  const int kvh = blockIdx.x, units = g.n_qb * g.group, nbins = g.n_kb + 1;
+  const int kvh = blockIdx.x, units = g.n_qb * g.group;
+  const int max_count = min(g.n_kb, g.words * 64);      // (a row keeps at most the key blocks of its own sequence)
+  const int nbins = max_count + 1;
   for (int b = threadIdx.x; b < nbins; b += blockDim.x) bin[b] = 0;
   __syncthreads();
   auto count_of = [&](int id) {
     const int c = row_counts[(size_t)(kvh * g.group + id % g.group) * g.n_qb + id / g.group];
-    return min(max(c, 0), g.n_kb);
+    return min(max(c, 0), max_count);
   };
   for (int id = threadIdx.x; id < units; id += blockDim.x) atomicAdd(&bin[count_of(id)], 1);
   __syncthreads();
@@ -625,7 +630,7 @@ struct WindowScan {
     id = order[(size_t)h * units + r];
     const int i = id / g.group, qh = h * g.group + id % g.group;
     if (row_counts[(size_t)qh * g.n_qb + i] <= min_count) return -1;
-    const int j_last = (i + 1) * bits_per_q - 1, last_word = j_last >> 6;
+    const int j_last = (seq_pos(g, i).il + 1) * bits_per_q - 1, last_word = j_last >> 6;
     if (w0 > last_word) return -1;
     const uint64_t* mrow = mask + ((size_t)qh * g.n_qb + i) * g.words;
     int c = 0;
@@ -834,7 +839,14 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
 // (independent of b_k).
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
                      const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st) {
-  const Geo g = make_geo(p);
+  Geo g = make_geo(p);
+  if (p->n_seqs > 0) {      // the per-block sequence table is the last part of the workspace
+    const int which = mask ? SALE_WS_SPARSE_ATTN : SALE_WS_DENSE_ATTN;
+    int32_t* table = (int32_t*)((uint8_t*)ws + sale_workspace_bytes(p, which) - seq_table_bytes(p));
+    const int rc = build_seq_table(p, table, st);
+    if (rc != SALE_OK) return rc;
+    g.seq_start = table;
+  }
   const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
   u32x4* kp = (u32x4*)ws;
   u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);

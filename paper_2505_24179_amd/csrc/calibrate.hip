@@ -82,7 +82,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
   int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
   if (!(tau0 > 0.0f && tau0 < 1.0f) || !(theta > 0.0f) || max_halvings < 0 || max_halvings > 64) return SALE_ERR_BAD_SHAPE;
-  if (p->n_q_heads > 4096 || p->batch > 4096) return SALE_ERR_UNSUPPORTED;
+  if (p->n_q_heads > 4096 || p->batch > 4096 || p->n_seqs > 0) return SALE_ERR_UNSUPPORTED;
   const size_t need = sale_workspace_bytes(p, SALE_WS_CALIBRATE);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 255)) return SALE_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;

@@ -55,7 +55,21 @@ struct Geo {
   int seg;         // segment size in key blocks (0 = no segment rule for the local area)
   int stats_causal;
   Strided sq, sk, sv, so;   // layouts of Q, K, V, O
+  // Variable-length batch: [n_qb] first 64-row block of the sequence that block i belongs to (device), or
+  // nullptr when every (batch, head) is one sequence.  n_qb, n_kb, seq then count the packed total and
+  // `words` the mask words of the longest sequence.
+  const int32_t* seq_start;
 };
+
+// Query block i of the packed token axis -> (its index inside its sequence, first key block of that sequence).
+struct SeqPos { int il, kb0; };
+__device__ __forceinline__ SeqPos seq_pos(const Geo& g, int i) {
+  const int s0 = g.seq_start ? g.seq_start[i] : 0;
+  SeqPos r;
+  r.il = i - s0;
+  r.kb0 = s0 * (kBlockQ / g.bk);
+  return r;
+}
 
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
   return __builtin_bit_cast(float, (unsigned)b << 16);
@@ -109,6 +123,10 @@ int validate_common(const sale_params_t* p, GeomClass cls);
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
                      const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st);
 Geo make_geo(const sale_params_t* p);
+// Variable-length batches: bytes of the per-block sequence table at the end of a workspace (0 without one), and
+// the kernel launches that fill it from the host offsets.
+size_t seq_table_bytes(const sale_params_t* p);
+int build_seq_table(const sale_params_t* p, int32_t* table, hipStream_t st);
 size_t calibrate_workspace_bytes(const sale_params_t* p);
 
 // 8-bit operands of the quantized Computation-Pass (quantize8.hip).

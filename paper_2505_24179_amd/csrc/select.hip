@@ -53,7 +53,8 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
     for (int s = 0; s < 8; ++s) qf[nt][s] = *(const bf16x8*)(row + 16 * s);
   }
   float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};
-  const int j_last = j_last_of(g, u.i), local = local_of(g, j_last);
+  const SeqPos sp = seq_pos(g, u.i);               // (variable-length batches: block indices inside the row's sequence)
+  const int j_last = j_last_of(g, sp.il), local = local_of(g, j_last);
   for (int j = 0; j <= j_last; ++j) {
     if (!in_sink_local(g, j, j_last, local)) { j = j_last - local; continue; }
     f32x16 acc[MT][2];
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
         for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      const uint16_t* row = k + row_off(g.sk, u.kvh, j * g.bk + 32 * mt + c) + 8 * h;
+      const uint16_t* row = k + row_off(g.sk, u.kvh, (sp.kb0 + j) * g.bk + 32 * mt + c) + 8 * h;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
         const bf16x8 a = *(const bf16x8*)(row + 16 * s);
@@ -74,8 +75,8 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
       }
     }
     // keys of this block that lie after a query row (only with SALE_FLAG_STATS_CAUSAL)
-    const bool mask_diag = g.stats_causal && (j + 1) * g.bk - 1 > u.i * 64;
-    const int ahead = j * g.bk - u.i * 64;      // first key of the block minus first query row
+    const bool mask_diag = g.stats_causal && (j + 1) * g.bk - 1 > sp.il * 64;
+    const int ahead = j * g.bk - sp.il * 64;      // first key of the block minus first query row
     // (VALU-bound: per score one half of a v_max3, one FMA that folds 1 / sqrt(d), log2(e) and the maximum,
     // one v_exp_f32 and one add; the causal select only where a block needs it)
     if (mask_diag) {
@@ -261,7 +262,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   const float* ks = k_scale + (size_t)kvh * g.n_kb;
   const size_t kgrp0 = (size_t)kvh * g.n_kb * MT;
 
-  const int j_last = j_last_of(g, i), local = local_of(g, j_last);
+  const SeqPos sp = seq_pos(g, i);
+  const int j_last = j_last_of(g, sp.il), local = local_of(g, j_last);
   int count[HPW];
 #pragma unroll
   for (int a = 0; a < HPW; ++a) count[a] = 0;
@@ -279,8 +281,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
       }
       i32x8 kf[MT][2];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) load_x6(k6, kgrp0 + (size_t)j * MT + mt, lane, kf[mt]);
-      const float sk = ks[j];
+      for (int mt = 0; mt < MT; ++mt) load_x6(k6, kgrp0 + (size_t)(sp.kb0 + j) * MT + mt, lane, kf[mt]);
+      const float sk = ks[sp.kb0 + j];
 #pragma unroll
       for (int a = 0; a < HPW; ++a) {
         f32x16 acc[MT][2];
@@ -323,7 +325,8 @@ __global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __
   th[0] = thr[(size_t)u.qh * g.seq + u.i * 64 + c];
   th[1] = thr[(size_t)u.qh * g.seq + u.i * 64 + 32 + c];
   uint64_t* mrow = mask + ((size_t)u.qh * g.n_qb + u.i) * g.words;
-  const int j_last = j_last_of(g, u.i), local = local_of(g, j_last);
+  const SeqPos sp = seq_pos(g, u.i);
+  const int j_last = j_last_of(g, sp.il), local = local_of(g, j_last);
   int count = 0;
   for (int wc = 0; wc < g.words; ++wc) {
     uint64_t word = 0;
@@ -340,7 +343,7 @@ __global__ __launch_bounds__(256) void select16_kernel(Geo g, const uint16_t* __
           for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const uint16_t* row = k + row_off(g.sk, u.kvh, j * g.bk + 32 * mt + c) + 8 * h;
+        const uint16_t* row = k + row_off(g.sk, u.kvh, (sp.kb0 + j) * g.bk + 32 * mt + c) + 8 * h;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
           const bf16x8 a = *(const bf16x8*)(row + 16 * s);
@@ -449,10 +452,16 @@ int run_select(const sale_params_t* p, const void* q, const void* k, const uint8
                const float* q_scale, const float* k_scale, const float* tau, int32_t tau_len, uint64_t* block_mask,
                int32_t* row_counts, float* m_out, float* l_out, void* ws, hipStream_t st) {
   const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
-  const Geo g = make_geo(p);
+  Geo g = make_geo(p);
   float* thr = (float*)ws;
   uint8_t* q6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
   uint8_t* k6 = q6 + (size_t)g.n_qh * (g.seq / 32) * kX6GroupBytes;
+  if (p->n_seqs > 0) {      // the per-block sequence table follows the operand copies
+    int32_t* table = (int32_t*)(k6 + (size_t)g.n_kvh * (g.seq / 32) * kX6GroupBytes);
+    const int rc = build_seq_table(p, table, st);
+    if (rc != SALE_OK) return rc;
+    g.seq_start = table;
+  }
   const long qgroups = (long)g.n_qh * (g.seq / 32), kgroups = (long)g.n_kvh * (g.seq / 32);
   if (!est16) {
     pack_fp6_kernel<<<dim3((unsigned)((qgroups + kgroups + 1) / 2)), dim3(256), 0, st>>>(q4, q6, qgroups, k4, k6, kgroups);

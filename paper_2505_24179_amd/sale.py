@@ -35,7 +35,8 @@ class _Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "seq_len", "head_dim",
         "block_q", "block_k", "sink_blocks", "local_blocks")] + [("flags", ctypes.c_uint32)] + \
-        [(n, ctypes.c_int64 * 3) for n in ("q_stride", "k_stride", "v_stride", "o_stride")]
+        [(n, ctypes.c_int64 * 3) for n in ("q_stride", "k_stride", "v_stride", "o_stride")] + \
+        [("n_seqs", ctypes.c_int32), ("cu_seqlens", ctypes.POINTER(ctypes.c_int32))]
 
 
 @dataclass(frozen=True)
@@ -50,6 +51,7 @@ class Params:
     sink_blocks: int = 1
     local_blocks: int = 4
     flags: int = 0
+    cu_seqlens: tuple = ()      # variable-length batch: token offsets (0, ..., seq_len) of the packed sequences
 
     def c(self, q=None, k=None, v=None, o=None) -> _Params:
         """The C struct.  Strides of Q, K, V, O are taken from the tensors given: zero (= contiguous) for a
@@ -60,6 +62,11 @@ class Params:
         for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o)):
             if t is not None and not t.is_contiguous():
                 getattr(cp, name)[:] = [int(x) for x in t.stride()[:3]]
+        if self.cu_seqlens:
+            offsets = (ctypes.c_int32 * len(self.cu_seqlens))(*self.cu_seqlens)
+            cp.n_seqs = len(self.cu_seqlens) - 1
+            cp.cu_seqlens = ctypes.cast(offsets, ctypes.POINTER(ctypes.c_int32))
+            cp._offsets = offsets      # (the host array lives as long as the struct)
         return cp
 
     @property
@@ -72,7 +79,11 @@ class Params:
 
     @property
     def words(self) -> int:
-        return (self.n_k + 63) // 64
+        """Mask words per row: those of the longest sequence."""
+        longest = self.seq_len
+        if self.cu_seqlens:
+            longest = max(b - a for a, b in zip(self.cu_seqlens[:-1], self.cu_seqlens[1:]))
+        return (longest // self.block_k + 63) // 64
 
 
 _vp, _sz, _i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32

@@ -177,4 +177,4 @@ def test_strides_are_validated(sale):
     assert call(q_stride=[0, 256 * 128, 128]) == -2                      # two batch entries on top of each other
     assert call(q_stride=[-8, 256 * 128, 128]) == -2
     # the struct grew at the end: a caller that fills only the leading fields gets contiguous tensors
-    assert ctypes.sizeof(good.c()) == 40 + 4 * 3 * 8
+    assert ctypes.sizeof(good.c()) == 40 + 4 * 3 * 8 + 16      # (+ n_seqs and the offsets pointer)
