@@ -21,7 +21,8 @@ against Eq. 4; structural invariants of the mask; attention with every block
 selected against brute-force causal softmax; the renormalisation identity for
 dropped blocks; the 8-bit Computation-Pass against the unquantized one (exact on
 the 8-bit grid, within the quantization-step bound elsewhere) and the softmax
-invariance of the K smoothing; the borderline band (is_borderline) against
+invariance of the K smoothing; the FP8 grid against literal values and a library conversion, the FP8 second
+product against closed forms (uniform and one-hot rows, a ones channel) and an error bound; the borderline band (is_borderline) against
 literal margins at |thr| <= 1, 10 and 100 and NaN margins.  No function here is
 "parity unpinned".
 """
@@ -355,6 +356,102 @@ def attention_block_int8qk(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_c
     if q_blk is not None:
         shift = np.asarray(q_blk, dtype=np.float64) @ np.asarray(k_mean, dtype=np.float64) / math.sqrt(geo.head_dim)
         lse = lse + shift
+    return o, lse
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.4 "Integration with SageAttention": low-precision second product (FP8 P and V)
+# --------------------------------------------------------------------------
+FP8_MAX = 448.0        # largest finite value of OCP FP8 E4M3 (4 exponent bits, bias 7, 3 mantissa bits, no infinities)
+
+
+def fp8_e4m3_round(x):
+    """Nearest value of the OCP FP8 E4M3 grid, ties to the even mantissa, saturating at +-448.
+    Grid: normal numbers 2^e * (1 + m/8), e = -6..8, m = 0..7 (2^8 * 1.875 = 480 is not a number: the top is 448);
+    subnormal numbers m * 2^-9, m = 0..7.  Returns float64 (every grid value is exact in it)."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.minimum(np.abs(x), FP8_MAX)
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6, 8)                        # below 2^-6 the spacing stays that of the subnormals
+    quantum = np.exp2(e - 3)
+    r = np.rint(a / quantum) * quantum           # np.rint rounds half to even; a / quantum is exact (power of two)
+    return np.sign(x) * np.minimum(r, FP8_MAX)
+
+
+def fp8_e4m3_encode(values) -> np.ndarray:
+    """Bit patterns (uint8: sign, 4 exponent bits, 3 mantissa bits) of values already on the E4M3 grid."""
+    v = np.asarray(values, dtype=np.float64)
+    a = np.abs(v)
+    sign = (np.signbit(v)).astype(np.uint8) << 7
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0))).astype(np.int64)
+    normal = a >= 2.0 ** -6
+    e = np.where(normal, e, -6)
+    mant = np.where(normal, np.rint((a / np.exp2(e) - 1.0) * 8), np.rint(a / 2.0 ** -9)).astype(np.int64)
+    expo = np.where(normal, e + 7, 0).astype(np.int64)
+    return (sign | (expo.astype(np.uint8) << 3) | mant.astype(np.uint8)).astype(np.uint8)
+
+
+def quantize_v_fp8(v: np.ndarray):
+    """V of the low-precision second product: per (head, channel) over all N tokens, in IEEE fp32,
+      amax = max |v|;  scale = amax / 448;  value = fp8_e4m3(v * (448 / amax))
+    (one fp32 multiply, then round to nearest even on the E4M3 grid; an all-zero channel gets scale 1, values 0).
+    v: float32 [H, N, d] -> (values float64 [H, N, d] on the E4M3 grid, scale float32 [H, d])."""
+    v = np.asarray(v, dtype=np.float32)
+    amax = np.max(np.abs(v), axis=1).astype(np.float32)                 # [H, d]
+    zero = amax == np.float32(0.0)
+    safe = np.where(zero, np.float32(1.0), amax)
+    scale = np.where(zero, np.float32(1.0), (safe / np.float32(FP8_MAX)).astype(np.float32)).astype(np.float32)
+    inv = np.where(zero, np.float32(0.0), (np.float32(FP8_MAX) / safe).astype(np.float32)).astype(np.float32)
+    scaled = (v * inv[:, None, :]).astype(np.float32)
+    return fp8_e4m3_round(scaled), scale
+
+
+def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: np.ndarray, v_scale: np.ndarray, mask_row):
+    """Eq. 1 for the rows of query block i from their attention weights s [b_q, N] with the second product in
+    FP8: the probabilities are taken block by block, online, as the quantized attention the method builds on does.
+    The kept keys are visited in ascending order in half-tiles of 32; a row's running maximum m is updated with
+    each half-tile, the half-tile's probabilities are P8 = fp8_e4m3(448 * exp(s - m)) (448: the top of the grid,
+    so that small probabilities stay above the subnormal range), and numerator and denominator are both sums of
+    those P8, rescaled by exp(m_old - m_new) whenever m grows:
+        O[r, c] = v_scale[c] * (sum_k P8[r, k] V8[k, c]) / (sum_k P8[r, k]),   lse = m + ln(sum_k P8 / 448).
+    v8: values of quantize_v_fp8 [N, d]; v_scale [d].  Returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    bq, n = s.shape
+    rows = i * geo.block_q + np.arange(bq)
+    keep = np.repeat(np.asarray(mask_row, dtype=bool), geo.block_k)
+    v8 = np.asarray(v8, dtype=np.float64)
+    m = np.full(bq, -np.inf)
+    num = np.zeros((bq, v8.shape[1]))
+    den = np.zeros(bq)
+    for t0 in range(0, n, 32):
+        if not keep[t0] or t0 > rows[-1]:
+            continue
+        cols = np.arange(t0, t0 + 32)
+        st = np.where(cols[None, :] <= rows[:, None], s[:, t0:t0 + 32], -np.inf)
+        m_new = np.maximum(m, st.max(axis=1))
+        alpha = np.where(np.isneginf(m_new), 1.0, np.exp(np.where(np.isneginf(m), -np.inf, m - np.where(np.isneginf(m_new), 0.0, m_new))))
+        m_safe = np.where(np.isneginf(m_new), 0.0, m_new)
+        p8 = fp8_e4m3_round(FP8_MAX * np.exp(st - m_safe[:, None]))
+        num = num * alpha[:, None] + p8 @ v8[t0:t0 + 32]
+        den = den * alpha + p8.sum(axis=1)
+        m = m_new
+    with np.errstate(divide="ignore", invalid="ignore"):
+        o = np.asarray(v_scale, dtype=np.float64)[None, :] * num / den[:, None]
+        lse = m + np.log(den / FP8_MAX)
+    return o, lse
+
+
+def attention_block_int8qk_fp8pv(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_codes, s_k, v8, v_scale, mask_row,
+                                 q_blk=None, k_mean=None):
+    """The fully quantized Computation-Pass: attention weights from the 8-bit operands as in
+    attention_block_int8qk, second product in FP8 as in attention_block_fp8pv_from_scores."""
+    assert geo.block_q == BLOCK8
+    a = int_products(q_codes_blk, k_codes).astype(np.float64)
+    s = a * float(s_q_i) * np.repeat(np.asarray(s_k, dtype=np.float64), BLOCK8)[None, :] / math.sqrt(geo.head_dim)
+    o, lse = attention_block_fp8pv_from_scores(geo, i, s, v8, v_scale, mask_row)
+    if q_blk is not None:
+        lse = lse + np.asarray(q_blk, dtype=np.float64) @ np.asarray(k_mean, dtype=np.float64) / math.sqrt(geo.head_dim)
     return o, lse
 
 
