@@ -87,6 +87,17 @@ typedef enum sale_status {
  * (head, 64-row block), exact integer products; mask, softmax and the product with V (bf16) are unchanged.
  * The operands are made inside the call (see sale_attn_int8_operands for their definition). */
 #define SALE_FLAG_ATTN_INT8_QK 8u
+/* Low-precision second product of the quantized Computation-Pass (Sec. 3.4 "Integration with SageAttention"; only
+ * together with SALE_FLAG_ATTN_INT8_QK and block_k = 64): V and the probabilities in OCP FP8 E4M3, fp32 accumulation.
+ *   V8 = fp8(V * 448 / amax) with amax per (KV head, channel) over all tokens (see sale_attn_fp8_operands);
+ *   the kept 64-key blocks of a row are visited in ascending order; with m the row's running maximum after a
+ *   block, that block's probabilities are P8 = fp8(448 * exp(S - m)), and
+ *   O[r][c] = (amax[c] / 448) * (sum_k P8[r][k] V8[k][c]) / (sum_k P8[r][k]),  lse = m + ln(sum_k P8 / 448),
+ *   both sums rescaled by exp(m_old - m_new) whenever m grows.
+ * This goes beyond the 16-bit second product of the default pass: every probability and every value of V carries a
+ * relative rounding error of up to 2^-4 (they average out over the keys), and the matrix unit adds the 64 products
+ * of an instruction with about 2^-14 relative precision. */
+#define SALE_FLAG_ATTN_FP8_PV 16u
 
 typedef struct sale_params {
   int32_t batch;
@@ -125,6 +136,7 @@ typedef struct sale_params {
 #define SALE_WS_DENSE_ATTN 3
 #define SALE_WS_CALIBRATE 4
 #define SALE_WS_INT8_OPERANDS 5
+#define SALE_WS_FP8_OPERANDS 6
 
 /* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
  * parameters are invalid). */
@@ -273,6 +285,19 @@ int sale_qk_int4_products(const sale_params_t* p, const uint8_t* q4, const uint8
 int sale_attn_int8_operands(const sale_params_t* p, const void* q, const void* k,
                             int8_t* q8, int8_t* k8, float* q_scale8, float* k_scale8, float* k_mean,
                             void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Parity hook: the FP8 operand of the low-precision second product (SALE_FLAG_ATTN_FP8_PV), made by the kernels the
+ * attention calls use.  Per (KV head, channel c), in IEEE fp32:
+ *   amax = max over the N tokens of |v|; v_scale = amax / 448; value = fp8_e4m3(v * (448 / amax))
+ * (OCP FP8 E4M3, round to nearest even; an all-zero channel gets scale 1 and values 0).
+ *
+ *   v8       out: uint8 [batch][n_kv_heads][N][d] bit patterns (sign, 4 exponent bits, 3 mantissa bits)
+ *   v_scale  out: fp32 [batch][n_kv_heads][d]
+ *   ws          : workspace of sale_workspace_bytes(p, SALE_WS_FP8_OPERANDS) bytes
+ */
+int sale_attn_fp8_operands(const sale_params_t* p, const void* v, uint8_t* v8, float* v_scale,
+                           void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Per-head threshold calibration (Sec. 3.3).  For every query head, starting from tau0 (the paper uses

@@ -411,29 +411,28 @@ def quantize_v_fp8(v: np.ndarray):
 def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: np.ndarray, v_scale: np.ndarray, mask_row):
     """Eq. 1 for the rows of query block i from their attention weights s [b_q, N] with the second product in
     FP8: the probabilities are taken block by block, online, as the quantized attention the method builds on does.
-    The kept keys are visited in ascending order in half-tiles of 32; a row's running maximum m is updated with
-    each half-tile, the half-tile's probabilities are P8 = fp8_e4m3(448 * exp(s - m)) (448: the top of the grid,
-    so that small probabilities stay above the subnormal range), and numerator and denominator are both sums of
-    those P8, rescaled by exp(m_old - m_new) whenever m grows:
+    The kept 64-key blocks are visited in ascending order; a row's running maximum m is updated with each block,
+    the block's probabilities are P8 = fp8_e4m3(448 * exp(s - m)) (448: the top of the grid, so that small
+    probabilities stay above the subnormal range), and numerator and denominator are both sums of those P8,
+    rescaled by exp(m_old - m_new) whenever m grows:
         O[r, c] = v_scale[c] * (sum_k P8[r, k] V8[k, c]) / (sum_k P8[r, k]),   lse = m + ln(sum_k P8 / 448).
-    v8: values of quantize_v_fp8 [N, d]; v_scale [d].  Returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    Needs b_k = 64.  v8: values of quantize_v_fp8 [N, d]; v_scale [d].  Returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    assert geo.block_k == 64
     bq, n = s.shape
     rows = i * geo.block_q + np.arange(bq)
-    keep = np.repeat(np.asarray(mask_row, dtype=bool), geo.block_k)
     v8 = np.asarray(v8, dtype=np.float64)
     m = np.full(bq, -np.inf)
     num = np.zeros((bq, v8.shape[1]))
     den = np.zeros(bq)
-    for t0 in range(0, n, 32):
-        if not keep[t0] or t0 > rows[-1]:
+    for j in range(geo.j_last(i) + 1):
+        if not mask_row[j]:
             continue
-        cols = np.arange(t0, t0 + 32)
-        st = np.where(cols[None, :] <= rows[:, None], s[:, t0:t0 + 32], -np.inf)
-        m_new = np.maximum(m, st.max(axis=1))
-        alpha = np.where(np.isneginf(m_new), 1.0, np.exp(np.where(np.isneginf(m), -np.inf, m - np.where(np.isneginf(m_new), 0.0, m_new))))
-        m_safe = np.where(np.isneginf(m_new), 0.0, m_new)
-        p8 = fp8_e4m3_round(FP8_MAX * np.exp(st - m_safe[:, None]))
-        num = num * alpha[:, None] + p8 @ v8[t0:t0 + 32]
+        cols = np.arange(j * 64, (j + 1) * 64)
+        st = np.where(cols[None, :] <= rows[:, None], s[:, cols], -np.inf)
+        m_new = np.maximum(m, st.max(axis=1))                       # (finite: key j * 64 <= every row of block i >= j)
+        alpha = np.where(np.isneginf(m), 0.0, np.exp(np.where(np.isneginf(m), 0.0, m) - m_new))
+        p8 = fp8_e4m3_round(FP8_MAX * np.exp(st - m_new[:, None]))
+        num = num * alpha[:, None] + p8 @ v8[cols]
         den = den * alpha + p8.sum(axis=1)
         m = m_new
     with np.errstate(divide="ignore", invalid="ignore"):

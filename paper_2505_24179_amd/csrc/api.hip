@@ -10,7 +10,7 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
   if (p->n_q_heads % p->n_kv_heads != 0) return SALE_ERR_BAD_SHAPE;
   if (p->sink_blocks < 0 || p->local_blocks < 1) return SALE_ERR_BAD_SHAPE;
   if (p->head_dim != kHeadDim) return SALE_ERR_UNSUPPORTED;
-  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL | SALE_FLAG_ATTN_INT8_QK)) return SALE_ERR_UNSUPPORTED;
+  if (p->flags & ~(SALE_FLAG_STATS_CAUSAL | SALE_FLAG_SELECT_16BIT | SALE_FLAG_SEGMENT_LOCAL | SALE_FLAG_ATTN_INT8_QK | SALE_FLAG_ATTN_FP8_PV)) return SALE_ERR_UNSUPPORTED;
   if ((p->block_q != 32 && p->block_q != 64) || (p->block_k != 32 && p->block_k != 64)) return SALE_ERR_UNSUPPORTED;
   if (p->n_seqs < 0 || (p->n_seqs > 0 && !p->cu_seqlens)) return SALE_ERR_BAD_SHAPE;
   int longest = p->seq_len;
@@ -24,6 +24,9 @@ int validate_common(const sale_params_t* p, GeomClass cls) {
     }
     if (p->flags & SALE_FLAG_ATTN_INT8_QK) return SALE_ERR_UNSUPPORTED;
   }
+  // the FP8 second product belongs to the fully quantized pass (8-bit first product) on 64-key blocks
+  if ((p->flags & SALE_FLAG_ATTN_FP8_PV) && (!(p->flags & SALE_FLAG_ATTN_INT8_QK) || p->block_k != kBlockK))
+    return SALE_ERR_UNSUPPORTED;
   if (cls != kGeomQuantize) {
     if (p->block_q != kBlockQ) return SALE_ERR_UNSUPPORTED;
     if (longest / p->block_k > kMaskWordsMax * 64) return SALE_ERR_UNSUPPORTED;
@@ -140,11 +143,14 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
       // (+ the 8-bit operand copies of the quantized Computation-Pass)
       return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
              (rows / kBlockQ) * ((1 + kMaskWordsMax / 2) * sizeof(int32_t) + 2048 * 16 + 256 * 4) + (128u << 10) + 16 +
-             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0) + seq_table_bytes(p);
+             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0) +
+             ((p->flags & SALE_FLAG_ATTN_FP8_PV) ? fp8_operand_bytes(p) : 0) + seq_table_bytes(p);
     case SALE_WS_CALIBRATE:
       return calibrate_workspace_bytes(p);
     case SALE_WS_INT8_OPERANDS:
       return (size_t)p->batch * p->n_kv_heads * (p->seq_len / 64) * 128 * sizeof(double);
+    case SALE_WS_FP8_OPERANDS:      // inverse scales + per-tile maxima
+      return (size_t)p->batch * p->n_kv_heads * (1 + p->seq_len / 64) * 128 * sizeof(float);
     default:
       return 0;
   }

@@ -130,8 +130,12 @@ struct Qk8 {
   const float* q_scale;   // [q head][N / 64]
   const float* k_scale;   // [kv head][N / 64]
   const float* k_mean;    // [kv head][128]: the mean key taken out of K before quantization
+  const u32x4* v8p;       // FP8 V in fragment order, 8 KB per 64 keys (PV8 only)
+  const float* v_scale;   // [kv head][128] (PV8 only)
 };
-template <int WAVES, bool BK32, bool QK8>
+// PV8 (with QK8, 64-key blocks): the second product in FP8 with v_mfma_f32_32x32x64_f8f6f4 - a quarter of the V
+// bytes and half the MFMA time of that product; see the PV8 section of the kernel.
+template <int WAVES, bool BK32, bool QK8, bool PV8 = false>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
                                                                const bf16x8* __restrict__ kp,
                                                                const bf16x8* __restrict__ vp, Qk8 q8o,
@@ -287,6 +291,137 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     return wc_it * 64 + b;
   };
 
+  if constexpr (PV8) {
+    // ---- fully quantized pass: 8-bit first product, FP8 second product ---------------------------------
+    // One 64-key block per step, nothing deferred: S^T = K8 Q8^T (16 MFMAs), causal mask on the diagonal block,
+    // ONE row maximum over the block's 64 keys, rescale, P8 = fp8(448 * exp2(x - m)) packed straight into the B
+    // operand of the FP8 MFMA (a lane's 16 + 16 accumulator values of the two half-tiles are its 32 contraction
+    // elements; the V8' copy is in the same key order), O^T += V8^T P8^T (8 MFMAs, K = 64).  The row sums are
+    // one more MFMA per query tile with an all-ones A operand: numerator and denominator are then sums of the
+    // SAME rounded probabilities.  The next block's K8 is requested once the first product has consumed this
+    // block's, the next V8 once the second product has.
+    static_assert(QK8 && !BK32, "the FP8 second product comes with the 8-bit first product on 64-key blocks");
+    const u32x4* const v8t = q8o.v8p + ((size_t)u.kvh * g.seq + (size_t)(u.i - il) * 64) * 8 + lane;   // 512 chunks per 64 keys
+    const float kLog2Top = 8.807354922057604f;      // log2(448)
+    i32x4 k8[2][4];
+    u32x4 v8[4][2];
+    float k_sc = 1.0f;
+    auto fetch_k = [&](int j) __attribute__((always_inline)) {
+      const i32x4* t = k8t + (size_t)j * 512;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) k8[mt][s] = t[(mt * 4 + s) * 64];
+      k_sc = ks8[j];
+    };
+    auto fetch_v = [&](int j) __attribute__((always_inline)) {
+      const u32x4* t = v8t + (size_t)j * 512;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) v8[dt][jj] = t[(dt * 2 + jj) * 64];
+    };
+    f32x16 lacc[2];      // every register: sum over the row's keys of P8 (all 32 rows of the ones product are equal)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) lacc[nt][r] = 2.0f * l_run[nt];      // (parked as half the sum: see below)
+    i32x8 ones8;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) ones8[w] = 0x38383838;                   // 1.0 in E4M3
+    int j = next_block();
+    if (j >= 0) {
+      fetch_k(j);
+      fetch_v(j);
+      while (true) {
+        const int jn = next_block();
+        i32x16 a[2][2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) a[mt][nt][r] = 0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+              a[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(k8[mt][s], qf8[nt][s], a[mt][nt], 0, 0, 0);
+        const float cj = k_sc * sq_cs;                 // raw integer product -> logit in log2 units
+        const bool diag = j == il;
+        fetch_k(jn >= 0 ? jn : j);                     // (unconditional: the last block re-reads its own)
+        float S[2][2][16];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              S[mt][nt][r] = (float)a[mt][nt][r];
+              if (diag && 32 * mt + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
+            }
+        float mx[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          float v = fmaxf(S[0][nt][0], S[1][nt][0]);
+#pragma unroll
+          for (int r = 1; r < 16; ++r) v = fmaxf(fmaxf(v, S[0][nt][r]), S[1][nt][r]);
+          mx[nt] = max_with_other_half(v) * cj;
+        }
+        if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] || mx[1] > m_run[1]) != 0ull) {
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) {
+            const float m_new = fmaxf(m_run[nt], mx[nt]);
+            const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
+            m_run[nt] = m_new;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) lacc[nt][r] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+          }
+        }
+        i32x8 p8[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const float mb = m_run[nt] - kLog2Top;       // exp2(x - m) * 448
+#pragma unroll
+          for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w], cj, -mb));
+              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 1], cj, -mb));
+              const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 2], cj, -mb));
+              const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 3], cj, -mb));
+              int word = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
+              word = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, word, true);
+              p8[nt][4 * mt + w] = word;
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          i32x8 va;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) { va[w] = (int)v8[dt][0][w]; va[4 + w] = (int)v8[dt][1][w]; }
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            oacc[dt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, p8[nt], oacc[dt][nt], 0, 0, 0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+          lacc[nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones8, p8[nt], lacc[nt], 0, 0, 0, 0, 0, 0);
+        if (jn < 0) break;
+        fetch_v(jn);
+        j = jn;
+      }
+    }
+    // the common tail adds the two lane halves' partial sums; here every lane already holds the whole sum
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) l_run[nt] = 0.5f * lacc[nt][0];
+  } else {
   // ---- pipeline stages ----------------------------------------------------------------
   // Half-tile score accumulators S[mt][nt] (keys 32mt.. x queries 32nt..) and the bf16 P^T operands
   // P[mt][nt][s2] made from them.  The MFMA stream and the softmax VALU stream of DIFFERENT half-tiles
@@ -508,6 +643,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     pv_half(1);
   }
 
+  }
+
   if (park) {
     f32x4* so = st_o + unit_flat * 2048 + lane;
 #pragma unroll
@@ -535,6 +672,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_run[nt] + swap_half(l_run[nt]);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    if constexpr (PV8) {      // O = v_scale[channel] * (sum P8 V8) / (sum P8)
+      const float* vs = q8o.v_scale + (size_t)u.kvh * kHeadDim + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 sc = *(const f32x4*)(vs + 32 * dt + 8 * q4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) oacc[dt][nt][4 * q4 + e] *= sc[e];
+        }
+    }
     const size_t row = (size_t)u.qh * g.seq + u.i * 64 + 32 * nt + c;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
@@ -553,7 +701,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
         }
       }
     if (lse && h == 0) {
-      float v = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(l_tot) : -INFINITY;
+      // (PV8: the sum is that of 448 p)
+      float v = l_tot > 0.0f ? m_run[nt] * 0.6931471805599453f + __logf(PV8 ? l_tot * (1.0f / 448.0f) : l_tot) : -INFINITY;
       if constexpr (QK8) {
         // The 8-bit logits are those of K minus its mean key, i.e. Eq. 1's logits of this row minus q_r . mean /
         // sqrt(d) (which the softmax cancels in O); lse is reported for Eq. 1's S, so the shift goes back in.
@@ -783,7 +932,7 @@ constexpr int kWindowMinWords = 4;   // sequences of up to 16K tokens use one sw
 
 namespace {
 
-template <bool BK32, bool QK8>
+template <bool BK32, bool QK8, bool PV8 = false>
 int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, Qk8 q8o, const uint64_t* mask,
                        const int32_t* row_counts, int32_t* order, int32_t* assign, uint16_t* o, float* o32, float* lse,
                        f32x4* st_o, float* st_ml, hipStream_t st) {
@@ -798,7 +947,7 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   if (!row_counts || g.words <= kWindowMinWords * f) {
     // (one sweep per row: every row reads K', V' of the whole sequence, and moving rows to another XCD costs
     // more L2 misses than the balance gains: 3.1 against 2.7 ms at 32K)
-    attn_rows_kernel<1, BK32, QK8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, nullptr,
+    attn_rows_kernel<1, BK32, QK8, PV8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, nullptr,
                                                              o, o32, lse, all, nullptr, nullptr);
     return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
   }
@@ -826,7 +975,7 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   for (int n = 0; n < launches; ++n) {
     // (the table holds the long rows only; the count filter applies to the tail)
     const RowFilter flt = {row_counts, -0x7FFFFFFF, kLongRow * f, n * step, step, (int)grid.x, launches, n};
-    attn_rows_kernel<1, BK32, QK8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(
+    attn_rows_kernel<1, BK32, QK8, PV8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(
         g, q, kp, vp, q8o, mask, order, assign + (size_t)n * grid.x, o, o32, lse, flt, st_o, st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
@@ -861,14 +1010,23 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
                                                                                     (const uint16_t*)v, g.sv, kp, vp);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const bool qk8 = (p->flags & SALE_FLAG_ATTN_INT8_QK) != 0;
-  Qk8 q8o = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  const bool pv8 = (p->flags & SALE_FLAG_ATTN_FP8_PV) != 0;      // (validated: only with qk8 and 64-key blocks)
+  Qk8 q8o = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   if (qk8) {
     // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
     const uintptr_t end = (uintptr_t)(assign + n_units * (kMaskWordsMax / 2)) + 16 + kLaneLoadBytes;
-    const Int8Operands w = carve_int8_operands(p, (void*)((end + 63) & ~(uintptr_t)63));
-    const int rc = launch_int8_operands(p, q, k, w, true, st);
+    const uintptr_t base8 = (end + 63) & ~(uintptr_t)63;
+    const Int8Operands w = carve_int8_operands(p, (void*)base8);
+    int rc = launch_int8_operands(p, q, k, w, true, st);
     if (rc != SALE_OK) return rc;
-    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale, w.k_mean};
+    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale, w.k_mean, nullptr, nullptr};
+    if (pv8) {      // then the FP8 copy of V (the 8-bit region's size is a multiple of 64 bytes)
+      const Fp8Operands w8 = carve_fp8_operands(p, (void*)(base8 + ((int8_operand_bytes(p) - 64 + 63) & ~(size_t)63)));
+      rc = launch_fp8_operands(p, v, w8, true, st);
+      if (rc != SALE_OK) return rc;
+      q8o.v8p = (const u32x4*)w8.v8;
+      q8o.v_scale = w8.v_scale;
+    }
   }
   const uint16_t* qq = (const uint16_t*)q;
   const bf16x8 *kpp = (const bf16x8*)kp, *vpp = (const bf16x8*)vp;
@@ -878,6 +1036,9 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
                                                   st_o, st_ml, st)
                  : launch_sparse_rows<true, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
                                                    lse, st_o, st_ml, st);
+    if (pv8)
+      return launch_sparse_rows<false, true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
+                                                   st_o, st_ml, st);
     return qk8 ? launch_sparse_rows<false, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
                                                  st_o, st_ml, st)
                : launch_sparse_rows<false, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
@@ -886,7 +1047,10 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   const int units = g.n_qb * g.group;
   const RowFilter all = {nullptr, 0, 0, -1, 0, -1, 0, 0};
   const dim3 grid((unsigned)(((units + 3) / 4) * g.n_kvh));
-  if (qk8)
+  if (pv8)
+    attn_rows_kernel<4, false, true, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o,
+                                                                      o32, lse, all, nullptr, nullptr);
+  else if (qk8)
     attn_rows_kernel<4, false, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o, o32,
                                                                 lse, all, nullptr, nullptr);
   else

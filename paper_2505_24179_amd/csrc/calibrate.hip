@@ -105,7 +105,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
   rc = sale_quantize_qk(p, q, k, c.q4, c.k4, c.qs, c.ks, stream);
   if (rc != SALE_OK) return finish(rc);
   sale_params_t full = *p;      // O of Sec. 3.3 is full attention in full precision
-  full.flags &= ~SALE_FLAG_ATTN_INT8_QK;
+  full.flags &= ~(SALE_FLAG_ATTN_INT8_QK | SALE_FLAG_ATTN_FP8_PV);
   rc = launch_attn_rows(&full, q, k, v, nullptr, nullptr, nullptr, c.o_full, nullptr, c.ws_att, st);
   if (rc != SALE_OK) return finish(rc);
 

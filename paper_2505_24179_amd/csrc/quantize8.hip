@@ -97,6 +97,132 @@ __global__ __launch_bounds__(256) void quantize8_kernel(const uint16_t* __restri
   }
 }
 
+// ---------------------------------------------------------------------------
+// V of the low-precision second product: OCP FP8 E4M3 values with one fp32 scale per (KV head, channel),
+//   amax = max over the head's N tokens of |v|;  scale = amax / 448;  value = fp8(v * (448 / amax))
+// (IEEE fp32, one multiply, round to nearest even; an all-zero channel gets scale 1 and values 0).
+// ---------------------------------------------------------------------------
+// Per (KV head, 64-row tile): partial[c] = max |v| over the tile's rows.
+__global__ __launch_bounds__(256) void vamax_kernel(const uint16_t* __restrict__ v, Strided lv, int tiles_per_head,
+                                                    float* __restrict__ partial) {
+  __shared__ float other[128];
+  const int c = threadIdx.x & 127, phase = threadIdx.x >> 7;
+  const uint16_t* rows = v + row_off(lv, blockIdx.x / tiles_per_head, (blockIdx.x % tiles_per_head) * 64 + phase * 32) + c;
+  float m = 0.0f;
+#pragma unroll 8
+  for (int r = 0; r < 32; ++r) m = fmaxf(m, fabsf(bf16_bits_to_float(rows[(size_t)r * lv.st])));
+  if (phase == 1) other[c] = m;
+  __syncthreads();
+  if (phase == 0) partial[(size_t)blockIdx.x * 128 + c] = fmaxf(m, other[c]);
+}
+
+// Per KV head: scale[c] = amax / 448 and inv[c] = 448 / amax (1 and 0 for an all-zero channel).
+__global__ __launch_bounds__(128) void vscale_kernel(const float* __restrict__ partial, int tiles, float* __restrict__ scale,
+                                                     float* __restrict__ inv) {
+  const int c = threadIdx.x;
+  const float* p = partial + (size_t)blockIdx.x * tiles * 128 + c;
+  float amax = 0.0f;
+  for (int t = 0; t < tiles; ++t) amax = fmaxf(amax, p[(size_t)t * 128]);
+  const bool zero = amax == 0.0f;
+  scale[blockIdx.x * 128 + c] = zero ? 1.0f : amax / 448.0f;
+  inv[blockIdx.x * 128 + c] = zero ? 0.0f : 448.0f / amax;
+}
+
+__device__ __forceinline__ uint32_t fp8x4(float a, float b, float c, float d) {
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+  return (uint32_t)w;
+}
+
+// One workgroup per (KV head, 64-key tile).
+// FRAG: the values go out as the A operand of v_mfma_f32_32x32x64_f8f6f4 for O^T += V^T P^T,
+//   [head][tile][dt 0..3][j 0..1][lane 0..63] 16 bytes: channel 32 dt + lane % 32 of the 16 keys
+//   32 j + 8 (e / 4) + 4 (lane / 32) + e % 4, e = 0..15
+// (the order in which the S^T accumulator registers of half-tile j hand P^T to the second product);
+// otherwise row-major [head][key][128 bytes].
+template <bool FRAG>
+__global__ __launch_bounds__(256) void quantize_v8_kernel(const uint16_t* __restrict__ v, Strided lv, int tiles_per_head,
+                                                          const float* __restrict__ inv, uint8_t* __restrict__ out) {
+  __shared__ float sv[64 * (kHeadDim + 1)];      // v * inv, rows padded by one bank
+  const int tid = threadIdx.x;
+  const size_t tile = blockIdx.x;
+  const int head = (int)(tile / tiles_per_head);
+  const uint16_t* vt = v + row_off(lv, head, (int)(tile % tiles_per_head) * 64);
+  const float* iv = inv + (size_t)head * 128;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int chunk = tid + 256 * r;
+    const int row = chunk >> 4, col = (chunk & 15) * 8;
+    const u32x4 w = *(const u32x4*)(vt + (size_t)row * lv.st + col);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sv[row * (kHeadDim + 1) + col + 2 * e] = __builtin_bit_cast(float, w[e] << 16) * iv[col + 2 * e];
+      sv[row * (kHeadDim + 1) + col + 2 * e + 1] = __builtin_bit_cast(float, w[e] & 0xFFFF0000u) * iv[col + 2 * e + 1];
+    }
+  }
+  __syncthreads();
+  if (FRAG) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int oc = tid + 256 * r;
+      const int lane = oc & 63, j = (oc >> 6) & 1, dt = oc >> 7;
+      const int d = 32 * dt + (lane & 31), h = lane >> 5;
+      u32x4 o4;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int key = 32 * j + 8 * w + 4 * h;      // e = 4 w .. 4 w + 3
+        o4[w] = fp8x4(sv[key * (kHeadDim + 1) + d], sv[(key + 1) * (kHeadDim + 1) + d], sv[(key + 2) * (kHeadDim + 1) + d],
+                      sv[(key + 3) * (kHeadDim + 1) + d]);
+      }
+      ((u32x4*)out)[tile * 512 + oc] = o4;
+    }
+  } else {
+    const int row = tid >> 2, cq = tid & 3;
+    const float* src = sv + row * (kHeadDim + 1) + 32 * cq;
+    u32x4 lo, hi;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      lo[w] = fp8x4(src[4 * w], src[4 * w + 1], src[4 * w + 2], src[4 * w + 3]);
+      hi[w] = fp8x4(src[16 + 4 * w], src[17 + 4 * w], src[18 + 4 * w], src[19 + 4 * w]);
+    }
+    u32x4* dst = (u32x4*)(out + (tile * 64 + row) * kHeadDim + 32 * cq);
+    dst[0] = lo;
+    dst[1] = hi;
+  }
+}
+
+size_t fp8_operand_bytes(const sale_params_t* p) {
+  const size_t kvrows = (size_t)p->batch * p->n_kv_heads * p->seq_len;
+  // V values | scales | inverse scales | per-tile maxima
+  return kvrows * kHeadDim + 2 * (size_t)p->batch * p->n_kv_heads * 128 * sizeof(float) + (kvrows / 64) * 128 * sizeof(float) + 64;
+}
+
+Fp8Operands carve_fp8_operands(const sale_params_t* p, void* base) {
+  const size_t kvrows = (size_t)p->batch * p->n_kv_heads * p->seq_len;
+  const size_t heads = (size_t)p->batch * p->n_kv_heads;
+  Fp8Operands w;
+  uint8_t* b = (uint8_t*)base;
+  w.v8 = b;                   b += kvrows * kHeadDim;
+  w.v_scale = (float*)b;      b += heads * 128 * sizeof(float);
+  w.v_inv = (float*)b;        b += heads * 128 * sizeof(float);
+  w.partial = (float*)b;
+  return w;
+}
+
+int launch_fp8_operands(const sale_params_t* p, const void* v, const Fp8Operands& w, bool frag, hipStream_t st) {
+  const int n_kvh = p->batch * p->n_kv_heads, tiles = p->seq_len / 64;
+  const Geo g = make_geo(p);
+  vamax_kernel<<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)v, g.sv, tiles, w.partial);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  vscale_kernel<<<dim3((unsigned)n_kvh), dim3(128), 0, st>>>(w.partial, tiles, w.v_scale, w.v_inv);
+  if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
+  if (frag)
+    quantize_v8_kernel<true><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)v, g.sv, tiles, w.v_inv, w.v8);
+  else
+    quantize_v8_kernel<false><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)v, g.sv, tiles, w.v_inv, w.v8);
+  return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
+}
+
 size_t int8_operand_bytes(const sale_params_t* p) {
   const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
   const size_t kvrows = (size_t)p->batch * p->n_kv_heads * p->seq_len;
@@ -156,4 +282,18 @@ extern "C" int sale_attn_int8_operands(const sale_params_t* p, const void* q, co
   w.q8 = q8; w.k8 = k8; w.q_scale = q_scale8; w.k_scale = k_scale8; w.k_mean = k_mean;
   w.partial = (double*)ws;
   return launch_int8_operands(p, q, k, w, false, (hipStream_t)stream);
+}
+
+extern "C" int sale_attn_fp8_operands(const sale_params_t* p, const void* v, uint8_t* v8, float* v_scale, void* ws,
+                                      size_t ws_bytes, void* stream) {
+  if (!p || !v || !v8 || !v_scale) return SALE_ERR_NULL_ARG;
+  int rc = validate_common(p, kGeomPath);
+  if (rc != SALE_OK) return rc;
+  const size_t need = sale_workspace_bytes(p, SALE_WS_FP8_OPERANDS);
+  if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
+  Fp8Operands w;
+  w.v8 = v8; w.v_scale = v_scale;
+  w.v_inv = (float*)ws;
+  w.partial = w.v_inv + (size_t)p->batch * p->n_kv_heads * 128;
+  return launch_fp8_operands(p, v, w, false, (hipStream_t)stream);
 }

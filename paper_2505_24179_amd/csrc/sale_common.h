@@ -82,12 +82,16 @@ __device__ __forceinline__ int mfma32_row(int r, int lane) { return 8 * (r >> 2)
 // Value held by the other half of the wave (lane ^ 32).
 __device__ __forceinline__ float swap_half(float x) { return __shfl_xor(x, 32, 64); }
 
-// max(x, x of lane ^ 32) without going through LDS: v_permlane32_swap leaves the lower half's
-// values in both halves of one result and the upper half's in the other.
+// max(x, x of lane ^ 32) without going through LDS: v_permlane32_swap exchanges the upper 32 lanes of its
+// first register with the lower 32 lanes of its second, so with x in both it leaves the lower half's values in
+// both halves of one register and the upper half's in the other.  Written as inline assembly on purpose: through
+// the builtin the compiler kept the instruction but dropped the maximum of the two results (it used the first
+// alone), which went unnoticed as long as every consumer only needed SOME common reference value per row.
+// (s_nop 1: the wait states the instruction needs after the VALU write of its operands.)
 __device__ __forceinline__ float max_with_other_half(float x) {
-  const unsigned u = __builtin_bit_cast(unsigned, x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+  float lo = x, hi = x;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+  return fmaxf(lo, hi);
 }
 
 // Unit = (flattened query head, 64-row query block): the work of one wave.
@@ -138,6 +142,16 @@ struct Int8Operands {
   float* k_mean;     // [kv head][128]
   double* partial;   // [kv head][N / 64][128] column sums per tile
 };
+// FP8 V of the low-precision second product (quantize8.hip).
+struct Fp8Operands {
+  uint8_t* v8;       // values: MFMA fragment order (attention) or row-major (parity hook)
+  float* v_scale;    // [kv head][128]
+  float* v_inv;      // [kv head][128]: 448 / amax
+  float* partial;    // [kv head][N / 64][128] per-tile maxima
+};
+size_t fp8_operand_bytes(const sale_params_t* p);
+Fp8Operands carve_fp8_operands(const sale_params_t* p, void* base);
+int launch_fp8_operands(const sale_params_t* p, const void* v, const Fp8Operands& w, bool frag, hipStream_t st);
 size_t int8_operand_bytes(const sale_params_t* p);
 Int8Operands carve_int8_operands(const sale_params_t* p, void* base);
 int launch_int8_operands(const sale_params_t* p, const void* q, const void* k, const Int8Operands& w, bool frag_k,

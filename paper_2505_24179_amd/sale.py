@@ -24,11 +24,13 @@ FLAG_STATS_CAUSAL = 1
 FLAG_SELECT_16BIT = 2
 FLAG_SEGMENT_LOCAL = 4
 FLAG_ATTN_INT8_QK = 8
+FLAG_ATTN_FP8_PV = 16
 WS_SELECT = 1
 WS_SPARSE_ATTN = 2
 WS_DENSE_ATTN = 3
 WS_CALIBRATE = 4
 WS_INT8_OPERANDS = 5
+WS_FP8_OPERANDS = 6
 
 
 class _Params(ctypes.Structure):
@@ -98,6 +100,7 @@ _SIGS = {
     "sale_dense_attn": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_qk_int4_products": (ctypes.c_int, [_pp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]),
     "sale_attn_int8_operands": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "sale_attn_fp8_operands": (ctypes.c_int, [_pp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "sale_calibrate_tau": (ctypes.c_int, [_pp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float, _i32, _vp, _vp, _vp,
                                           _vp, _sz, _vp]),
 }
@@ -317,6 +320,19 @@ def attn_int8_operands(p: Params, q, k):
     _check(_lib.sale_attn_int8_operands(ctypes.byref(p.c(q, k)), _ptr(q), _ptr(k), _ptr(q8), _ptr(k8), _ptr(qs), _ptr(ks),
                                         _ptr(mean), _ptr(ws), ws.numel(), _stream()))
     return q8, k8, qs, ks, mean
+
+
+def attn_fp8_operands(p: Params, v):
+    """-> (v8 uint8 [B,Hkv,N,d] FP8 E4M3 bit patterns, v_scale f32 [B,Hkv,d]): the FP8 operand of the low-precision
+    second product (parity hook)."""
+    dev = v.device
+    _expect_bhnd("v", v, p, p.n_kv_heads)
+    v8 = torch.empty(p.batch, p.n_kv_heads, p.seq_len, p.head_dim, dtype=torch.uint8, device=dev)
+    vs = torch.empty(p.batch, p.n_kv_heads, p.head_dim, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(1, workspace_bytes(p, WS_FP8_OPERANDS)), dtype=torch.uint8, device=dev)
+    _check(_lib.sale_attn_fp8_operands(ctypes.byref(p.c(v=v)), _ptr(v), _ptr(v8), _ptr(vs), _ptr(ws), _expect_ws(ws, 0),
+                                       _stream()))
+    return v8, vs
 
 
 def calibrate_tau(p: Params, q, k, v, tau0: float = 0.008, theta: float = 0.4, max_halvings: int = 8, ws=None):

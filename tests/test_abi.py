@@ -25,7 +25,8 @@ def _declared_functions():
 def test_header_functions_are_exported(sale):
     names = _declared_functions()
     assert {"sale_quantize_qk", "sale_select", "sale_sparse_attn", "sale_dense_attn", "sale_calibrate_tau",
-            "sale_qk_int4_products", "sale_attn_int8_operands", "sale_workspace_bytes", "sale_status_string"} <= set(names)
+            "sale_qk_int4_products", "sale_attn_int8_operands", "sale_attn_fp8_operands", "sale_select_static",
+            "sale_workspace_bytes", "sale_status_string"} <= set(names)
     lib = sale.raw()
     for n in names:
         assert hasattr(lib, n), f"{n} declared in sale.h but not exported"
@@ -63,7 +64,9 @@ def test_argument_validation_launches_nothing(sale):
     assert _call_quant(sale, sale.Params(1, 4, 3, 256)) == -2          # heads not divisible
     assert _call_quant(sale, sale.Params(1, 4, 2, 256, head_dim=64)) == -3
     assert _call_quant(sale, sale.Params(1, 4, 2, 256, block_q=16, block_k=16)) == -3
-    assert _call_quant(sale, sale.Params(1, 4, 2, 256, flags=16)) == -3
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, flags=32)) == -3
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, flags=16)) == -3           # FP8 second product without the 8-bit first
+    assert _call_quant(sale, sale.Params(1, 4, 2, 256, block_k=32, flags=24)) == -3   # ... or on 32-key blocks
     # select: query blocks must be 64 rows, at most 4096 key blocks; workspace too small; bad tau_len
     sel = lib.sale_select
     p3232 = sale.Params(1, 4, 2, 256, block_q=32, block_k=32)
