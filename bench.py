@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_INT8_TOPS = 5000.0       # MI355X dense int8 MFMA
+PEAK_FP8_TFLOPS = 5000.0      # MI355X dense fp8 MFMA
 PEAK_FP6_TFLOPS = 10100.0     # MI355X dense fp6 MFMA
 PEAK_HBM_GBS = 8000.0
 
@@ -91,6 +92,8 @@ def main() -> int:
     ap.add_argument("--segment-local", action="store_true", help="segment rule for the local area (Appendix C)")
     ap.add_argument("--attn-int8-qk", action="store_true",
                     help="quantized Computation-Pass (Sec. 3.4): 8-bit Q, K in the first product of sparse AND dense attention")
+    ap.add_argument("--attn-fp8-pv", action="store_true",
+                    help="fully quantized Computation-Pass: --attn-int8-qk plus the FP8 second product (64x64 blocks)")
     ap.add_argument("--cpu-units", type=int, default=96, help="oracle sample size (0 = skip the CPU baseline)")
     ap.add_argument("--no-lengths", dest="lengths", action="store_false",
                     help="skip the 32K and 64K legs that the default 128K run adds (object `lengths`)")
@@ -107,7 +110,10 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
-    flags = (sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0) | (sale.FLAG_ATTN_INT8_QK if args.attn_int8_qk else 0)
+    if args.attn_fp8_pv:
+        args.attn_int8_qk = True
+    flags = (sale.FLAG_SEGMENT_LOCAL if args.segment_local else 0) | (sale.FLAG_ATTN_INT8_QK if args.attn_int8_qk else 0) | \
+            (sale.FLAG_ATTN_FP8_PV if args.attn_fp8_pv else 0)
 
     def measure(w, steps, warmup, dense_steps):
         """One workload: K timed steps of quantize -> select -> sparse attention (HIP events around every stage on
@@ -171,8 +177,8 @@ def main() -> int:
         middle_pairs = sum(max(0, (i + 1) * kpq - p.sink_blocks - p.local_blocks) for i in range(n_q)) * w.n_q_heads
         quant_bytes = (w.n_q_heads + w.n_kv_heads) * w.seq_len * (256 + 64) + (w.n_q_heads + w.n_kv_heads) * n_q * 4
         bf16_peak = PEAK_BF16_TFLOPS
-        if args.attn_int8_qk:       # the first product runs at the int8 MFMA rate, the second at the bf16 rate
-            bf16_peak = 2.0 / (1.0 / PEAK_BF16_TFLOPS + 1.0 / PEAK_INT8_TOPS)
+        if args.attn_int8_qk:       # the first product runs at the int8 MFMA rate, the second at the bf16 (or FP8) rate
+            bf16_peak = 2.0 / (1.0 / (PEAK_FP8_TFLOPS if args.attn_fp8_pv else PEAK_BF16_TFLOPS) + 1.0 / PEAK_INT8_TOPS)
         kernels = {
             "quantize": {"bound": "hbm", "achieved": quant_bytes / (quant_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "ms": quant_ms},
@@ -248,7 +254,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "seq_len": w.seq_len, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "block": f"64x{args.block_k}", "segment_local": bool(args.segment_local),
-                   "attn_int8_qk": bool(args.attn_int8_qk), "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
+                   "attn_int8_qk": bool(args.attn_int8_qk), "attn_fp8_pv": bool(args.attn_fp8_pv), "tau": w.tau, "rho": w.rho, "n_heavy": w.n_heavy,
                    "seed": w.seed},
         "stages_ms": fig["stages_ms"],
         "density": fig["density"],

@@ -96,7 +96,9 @@ typedef enum sale_status {
  *   both sums rescaled by exp(m_old - m_new) whenever m grows.
  * This goes beyond the 16-bit second product of the default pass: every probability and every value of V carries a
  * relative rounding error of up to 2^-4 (they average out over the keys), and the matrix unit adds the 64 products
- * of an instruction with about 2^-14 relative precision. */
+ * of an instruction with about 2^-14 relative precision.  The codes P8 are decided in fp32 with the hardware exp2:
+ * a probability within rounding distance of the midpoint of two codes may take either, which moves lse by at most
+ * (that term's share of the row sum) / 8; apart from such rows lse keeps the accuracy stated at sale_sparse_attn. */
 #define SALE_FLAG_ATTN_FP8_PV 16u
 
 typedef struct sale_params {

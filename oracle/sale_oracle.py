@@ -408,7 +408,8 @@ def quantize_v_fp8(v: np.ndarray):
     return fp8_e4m3_round(scaled), scale
 
 
-def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: np.ndarray, v_scale: np.ndarray, mask_row):
+def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: np.ndarray, v_scale: np.ndarray, mask_row,
+                                      arg_tol=None):
     """Eq. 1 for the rows of query block i from their attention weights s [b_q, N] with the second product in
     FP8: the probabilities are taken block by block, online, as the quantized attention the method builds on does.
     The kept 64-key blocks are visited in ascending order; a row's running maximum m is updated with each block,
@@ -416,7 +417,13 @@ def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: 
     probabilities stay above the subnormal range), and numerator and denominator are both sums of those P8,
     rescaled by exp(m_old - m_new) whenever m grows:
         O[r, c] = v_scale[c] * (sum_k P8[r, k] V8[k, c]) / (sum_k P8[r, k]),   lse = m + ln(sum_k P8 / 448).
-    Needs b_k = 64.  v8: values of quantize_v_fp8 [N, d]; v_scale [d].  Returns (O fp64 [b_q, d], lse fp64 [b_q])."""
+    Needs b_k = 64.  v8: values of quantize_v_fp8 [N, d]; v_scale [d].  Returns (O fp64 [b_q, d], lse fp64 [b_q]).
+
+    arg_tol (None, or one absolute tolerance per key block [n_k]): P8 is a rounding decision, so an implementation
+    whose argument s - m is off by up to arg_tol may round a probability near the midpoint of two codes to the
+    other one.  With arg_tol the function also returns how far that can move the results: (O, lse, o_slack
+    [b_q, d], lse_slack [b_q]), computed by rounding every probability at both ends of its tolerance interval
+    and carrying the differences through the same sums (zero for a row none of whose probabilities can flip)."""
     assert geo.block_k == 64
     bq, n = s.shape
     rows = i * geo.block_q + np.arange(bq)
@@ -424,6 +431,8 @@ def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: 
     m = np.full(bq, -np.inf)
     num = np.zeros((bq, v8.shape[1]))
     den = np.zeros(bq)
+    num_slack = np.zeros_like(num)
+    den_slack = np.zeros_like(den)
     for j in range(geo.j_last(i) + 1):
         if not mask_row[j]:
             continue
@@ -434,24 +443,36 @@ def attention_block_fp8pv_from_scores(geo: Geometry, i: int, s: np.ndarray, v8: 
         p8 = fp8_e4m3_round(FP8_MAX * np.exp(st - m_new[:, None]))
         num = num * alpha[:, None] + p8 @ v8[cols]
         den = den * alpha + p8.sum(axis=1)
+        if arg_tol is not None:
+            t = float(np.asarray(arg_tol, dtype=np.float64).reshape(-1)[j if np.ndim(arg_tol) else 0])
+            hi = fp8_e4m3_round(np.minimum(FP8_MAX * np.exp(st - m_new[:, None] + t), FP8_MAX))
+            lo = fp8_e4m3_round(FP8_MAX * np.exp(st - m_new[:, None] - t))
+            num_slack = num_slack * alpha[:, None] + (hi - lo) @ np.abs(v8[cols])
+            den_slack = den_slack * alpha + (hi - lo).sum(axis=1)
         m = m_new
+    vs = np.asarray(v_scale, dtype=np.float64)[None, :]
     with np.errstate(divide="ignore", invalid="ignore"):
-        o = np.asarray(v_scale, dtype=np.float64)[None, :] * num / den[:, None]
+        o = vs * num / den[:, None]
         lse = m + np.log(den / FP8_MAX)
-    return o, lse
+        if arg_tol is None:
+            return o, lse
+        rest = np.maximum(den - den_slack, 1e-300)[:, None]         # |d(num/den)| <= (d num + |num/den| d den) / (den - d den)
+        o_slack = vs * (num_slack + np.abs(num / den[:, None]) * den_slack[:, None]) / rest
+        lse_slack = -np.log1p(-np.minimum(den_slack / den, 0.5))    # |d ln den| <= -ln(1 - d den / den)
+    return o, lse, np.nan_to_num(o_slack), np.nan_to_num(lse_slack)
 
 
 def attention_block_int8qk_fp8pv(geo: Geometry, i: int, q_codes_blk, s_q_i: float, k_codes, s_k, v8, v_scale, mask_row,
-                                 q_blk=None, k_mean=None):
+                                 q_blk=None, k_mean=None, arg_tol=None):
     """The fully quantized Computation-Pass: attention weights from the 8-bit operands as in
-    attention_block_int8qk, second product in FP8 as in attention_block_fp8pv_from_scores."""
+    attention_block_int8qk, second product in FP8 as in attention_block_fp8pv_from_scores (arg_tol as there)."""
     assert geo.block_q == BLOCK8
     a = int_products(q_codes_blk, k_codes).astype(np.float64)
     s = a * float(s_q_i) * np.repeat(np.asarray(s_k, dtype=np.float64), BLOCK8)[None, :] / math.sqrt(geo.head_dim)
-    o, lse = attention_block_fp8pv_from_scores(geo, i, s, v8, v_scale, mask_row)
+    out = list(attention_block_fp8pv_from_scores(geo, i, s, v8, v_scale, mask_row, arg_tol))
     if q_blk is not None:
-        lse = lse + np.asarray(q_blk, dtype=np.float64) @ np.asarray(k_mean, dtype=np.float64) / math.sqrt(geo.head_dim)
-    return o, lse
+        out[1] = out[1] + np.asarray(q_blk, dtype=np.float64) @ np.asarray(k_mean, dtype=np.float64) / math.sqrt(geo.head_dim)
+    return tuple(out)
 
 
 def dense_mask(geo: Geometry) -> np.ndarray:

@@ -135,6 +135,8 @@ struct Qk8 {
 };
 // PV8 (with QK8, 64-key blocks): the second product in FP8 with v_mfma_f32_32x32x64_f8f6f4 - a quarter of the V
 // bytes and half the MFMA time of that product; see the PV8 section of the kernel.
+constexpr float kIntOffset = 12582912.0f;            // 1.5 * 2^23, bit pattern 0x4B400000 (see qk_half)
+
 template <int WAVES, bool BK32, bool QK8, bool PV8 = false>
 __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint16_t* __restrict__ q,
                                                                const bf16x8* __restrict__ kp,
@@ -329,92 +331,98 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     i32x8 ones8;
 #pragma unroll
     for (int w = 0; w < 8; ++w) ones8[w] = 0x38383838;                   // 1.0 in E4M3
+    i32x16 magic;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) magic[r] = 0x4B400000;
+    // one block; `diag`: apply the causal mask (the diagonal block) - a variant of its own, so that the other
+    // blocks pay nothing for it
+    auto step8 = [&](int jn_or_j, auto diag) __attribute__((always_inline)) {
+      // (the accumulators start at the bit pattern of kIntOffset and are read as floats, as in qk_half)
+      i32x16 a[2][2];
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            a[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(k8[mt][s], qf8[nt][s], s == 0 ? magic : a[mt][nt], 0, 0, 0);
+      const float cj = k_sc * sq_cs;                 // raw integer product -> logit in log2 units
+      const float off = kIntOffset * cj;                 // what the offset amounts to in logit units
+      fetch_k(jn_or_j);                              // (unconditional: the last block re-reads its own)
+      float S[2][2][16];
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            S[mt][nt][r] = int_bits_as_float(a[mt][nt][r]);
+            if constexpr (decltype(diag)::value) {
+              if (32 * mt + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
+            }
+          }
+      float mx[2];
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        float v = fmaxf(S[0][nt][0], S[1][nt][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) v = fmaxf(fmaxf(v, S[0][nt][r]), S[1][nt][r]);
+        mx[nt] = __builtin_fmaf(max_with_other_half(v), cj, -off);
+      }
+      if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] || mx[1] > m_run[1]) != 0ull) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const float m_new = fmaxf(m_run[nt], mx[nt]);
+          const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
+          m_run[nt] = m_new;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) lacc[nt][r] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
+        }
+      }
+      i32x8 p8[2];
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const float mb = m_run[nt] - kLog2Top + off;       // exp2(x - m) * 448, x = (S - offset) * cj
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w], cj, -mb));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 1], cj, -mb));
+            const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 2], cj, -mb));
+            const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 3], cj, -mb));
+            int word = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
+            word = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, word, true);
+            p8[nt][4 * mt + w] = word;
+          }
+      }
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
+        i32x8 va;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { va[w] = (int)v8[dt][0][w]; va[4 + w] = (int)v8[dt][1][w]; }
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+          oacc[dt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, p8[nt], oacc[dt][nt], 0, 0, 0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+        lacc[nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones8, p8[nt], lacc[nt], 0, 0, 0, 0, 0, 0);
+      fetch_v(jn_or_j);                              // (unconditional as well: every path leaves the same loads in flight,
+                                                     // so the next step waits for exactly the K8 it needs, not for everything)
+    };
     int j = next_block();
     if (j >= 0) {
       fetch_k(j);
       fetch_v(j);
       while (true) {
         const int jn = next_block();
-        i32x16 a[2][2];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) a[mt][nt][r] = 0;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-              a[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(k8[mt][s], qf8[nt][s], a[mt][nt], 0, 0, 0);
-        const float cj = k_sc * sq_cs;                 // raw integer product -> logit in log2 units
-        const bool diag = j == il;
-        fetch_k(jn >= 0 ? jn : j);                     // (unconditional: the last block re-reads its own)
-        float S[2][2][16];
-#pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              S[mt][nt][r] = (float)a[mt][nt][r];
-              if (diag && 32 * mt + mfma32_row(r, lane) > 32 * nt + c) S[mt][nt][r] = -INFINITY;
-            }
-        float mx[2];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          float v = fmaxf(S[0][nt][0], S[1][nt][0]);
-#pragma unroll
-          for (int r = 1; r < 16; ++r) v = fmaxf(fmaxf(v, S[0][nt][r]), S[1][nt][r]);
-          mx[nt] = max_with_other_half(v) * cj;
-        }
-        if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] || mx[1] > m_run[1]) != 0ull) {
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt) {
-            const float m_new = fmaxf(m_run[nt], mx[nt]);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[nt] - m_new);
-            m_run[nt] = m_new;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) lacc[nt][r] *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) oacc[dt][nt][r] *= alpha;
-          }
-        }
-        i32x8 p8[2];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          const float mb = m_run[nt] - kLog2Top;       // exp2(x - m) * 448
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w], cj, -mb));
-              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 1], cj, -mb));
-              const float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 2], cj, -mb));
-              const float p3 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[mt][nt][4 * w + 3], cj, -mb));
-              int word = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
-              word = __builtin_amdgcn_cvt_pk_fp8_f32(p2, p3, word, true);
-              p8[nt][4 * mt + w] = word;
-            }
-        }
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          i32x8 va;
-#pragma unroll
-          for (int w = 0; w < 4; ++w) { va[w] = (int)v8[dt][0][w]; va[4 + w] = (int)v8[dt][1][w]; }
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-            oacc[dt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(va, p8[nt], oacc[dt][nt], 0, 0, 0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-          lacc[nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones8, p8[nt], lacc[nt], 0, 0, 0, 0, 0, 0);
+        if (j == il) step8(jn >= 0 ? jn : j, std::true_type{}); else step8(jn >= 0 ? jn : j, std::false_type{});
         if (jn < 0) break;
-        fetch_v(jn);
         j = jn;
       }
     }
@@ -435,7 +443,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 
   auto qk_half = [&](int mt) __attribute__((always_inline)) {                       // S[mt][*] = K(half mt) Q^T
     if constexpr (QK8) {
-      i32x16 a0 = {0}, a1 = {0};
+      // The integer accumulators start at the bit pattern of kIntOffset = 1.5 * 2^23: an integer x with |x| < 2^22
+      // added to it (the sums are below 127 * 127 * 128 < 2^21) gives the bit pattern of the FLOAT kIntOffset + x,
+      // so the sums are read as floats without a conversion each; the offset leaves with the scaling FMAs.
+      i32x16 a0, a1;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) a0[r] = a1[r] = 0x4B400000;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         a0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(kf8[mt][s], qf8[0][s], a0, 0, 0, 0);
@@ -443,8 +456,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        S[mt][0][r] = (float)a0[r];
-        S[mt][1][r] = (float)a1[r];
+        S[mt][0][r] = int_bits_as_float(a0[r]);
+        S[mt][1][r] = int_bits_as_float(a1[r]);
       }
     } else {
 #pragma unroll
@@ -484,7 +497,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
       float v = fmaxf(S[mt][nt][0], S[mt][nt][1]);
 #pragma unroll
       for (int r = 2; r < 16; r += 2) v = fmaxf(fmaxf(v, S[mt][nt][r]), S[mt][nt][r + 1]);
-      mx[nt] = max_with_other_half(v) * cl[mt];
+      if constexpr (QK8) mx[nt] = __builtin_fmaf(max_with_other_half(v), cl[mt], -kIntOffset * cl[mt]);
+      else mx[nt] = max_with_other_half(v) * cl[mt];
     }
   };
   // Lazy rescale: O and l are rescaled only when some row's maximum grew (exact: otherwise the factor
@@ -518,8 +532,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
     ones[0] = (__bf16)1.0f; ones[1] = (__bf16)1.0f;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      const float mb = (BK32 && m_run[nt] == -INFINITY) ? 0.0f : m_run[nt];
       const float ch = cl[mt];
+      float mb = (BK32 && m_run[nt] == -INFINITY) ? 0.0f : m_run[nt];
+      if constexpr (QK8) mb += kIntOffset * ch;        // S carries the accumulators' offset
       float sum = l_run[nt];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {

@@ -82,6 +82,14 @@ __device__ __forceinline__ int mfma32_row(int r, int lane) { return 8 * (r >> 2)
 // Value held by the other half of the wave (lane ^ 32).
 __device__ __forceinline__ float swap_half(float x) { return __shfl_xor(x, 32, 64); }
 
+// Reads an integer register as a float.  The empty statement hides the value's origin from the optimizer: with
+// this compiler, float arithmetic on elements 1.. of an integer vector that an intrinsic returned and that is
+// reinterpreted as floats was folded away as if those elements were NaN (only element 0 survived a maximum).
+__device__ __forceinline__ float int_bits_as_float(int x) {
+  asm("" : "+v"(x));
+  return __builtin_bit_cast(float, x);
+}
+
 // max(x, x of lane ^ 32) without going through LDS: v_permlane32_swap exchanges the upper 32 lanes of its
 // first register with the lower 32 lanes of its second, so with x in both it leaves the lower half's values in
 // both halves of one register and the upper half's in the other.  Written as inline assembly on purpose: through

@@ -143,3 +143,38 @@ def test_int8qk_fp8pv_composes_the_two():
     np.testing.assert_allclose(lse - lse2, q[rs].astype(np.float64) @ mean[0].astype(np.float64) / math.sqrt(d), atol=1e-12)
     o16, _ = so.attention_block_int8qk(geo, i, qc[0][rs], qs[0, i], kc[0], ks[0], v, row)
     assert 1e-4 < np.abs(o - o16).max() < 0.1
+
+
+def test_fp8_flip_slack_bounds_the_effect_of_a_perturbed_argument():
+    """arg_tol: with tolerance 0 the slack is 0; shifting every (row, key block) group of scores by up to
+    arg_tol / 2 (so that s - m moves by up to arg_tol) changes O and lse by no more than the slack plus the
+    first-order effect of the shift itself; rows with no probability near a midpoint have zero slack, and some
+    rows do flip (the bound is not vacuous)."""
+    n, d = 512, 16
+    rng = np.random.default_rng(5)
+    v = rng.normal(size=(1, n, d)).astype(np.float32)
+    val, scale = so.quantize_v_fp8(v)
+    geo = _geo(n)
+    i, row = 7, so.dense_mask(_geo(n))[7]
+    s = rng.normal(size=(64, n)) * 2.5
+    o, lse, os0, ls0 = so.attention_block_fp8pv_from_scores(geo, i, s, val[0], scale[0], row, arg_tol=0.0)
+    assert not os0.any() and not ls0.any()
+    o_b, lse_b = so.attention_block_fp8pv_from_scores(geo, i, s, val[0], scale[0], row)
+    np.testing.assert_array_equal(o, o_b); np.testing.assert_array_equal(lse, lse_b)
+    tol = np.full(geo.n_k, 2e-3); tol[0] = 8e-3                     # one tolerance per key block
+    _, _, o_slack, lse_slack = so.attention_block_fp8pv_from_scores(geo, i, s, val[0], scale[0], row, arg_tol=tol)
+    assert (lse_slack > 0).sum() > 8 and (o_slack >= 0).all()
+    seen = 0.0
+    for trial in range(8):
+        u = rng.uniform(-0.5, 0.5, size=(64, geo.n_k)) * tol[None, :]
+        o2, lse2 = so.attention_block_fp8pv_from_scores(geo, i, s + np.repeat(u, 64, axis=1), val[0], scale[0], row)
+        first_order = tol.max()                                     # d lse / d s and d O / d s (|V| <= amax) of the exact map
+        assert (np.abs(lse2 - lse) <= lse_slack + first_order).all()
+        assert (np.abs(o2 - o) <= o_slack + 2 * first_order * np.abs(v).max()).all()
+        _, e0 = so.attention_block_from_scores(geo, i, s, v[0], row)
+        _, e1 = so.attention_block_from_scores(geo, i, s + np.repeat(u, 64, axis=1), v[0], row)
+        seen = max(seen, np.abs((lse2 - lse) - (e1 - e0)).max())
+    assert seen > 2e-4                                              # codes did flip: not the smooth change of the exact lse
+    quiet = lse_slack == 0
+    if quiet.any():                                                 # no flip possible: only the first-order effect
+        assert (np.abs(lse2 - lse)[quiet] <= first_order).all()
