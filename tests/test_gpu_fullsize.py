@@ -8,7 +8,8 @@ import torch
 
 from oracle import sale_oracle as so
 from paper_2505_24179_amd import inputs
-from tests.parity_utils import LSE_ATOL, check_output, compare_mask_row, words_to_bool
+from tests.parity_utils import (LSE_ATOL, check_lse_fp8, check_output, check_output_fp8, compare_mask_row, fp8_arg_tol,
+                                words_to_bool)
 
 pytestmark = pytest.mark.gpu
 
@@ -167,14 +168,17 @@ def test_full_size_sampled_parity_paper_shape_64x32(sale, name, n_units):
     assert soft <= 4
 
 
+@pytest.mark.parametrize("fp8", [False, True], ids=["pv16", "pv8"])
 @pytest.mark.parametrize("name,n_units", [("gqa2-36k-long-rows", 12), ("llama31-8b-layer-128k", 8)])
-def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
+def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units, fp8):
     """The quantized Computation-Pass (Sec. 3.4 "Integration with SageAttention") at full size, windowed sweep
-    included: sampled units against the oracle that takes the same 8-bit operands."""
+    included: sampled units against the oracle that takes the same 8-bit operands; with the second product in
+    16 bit and in FP8 (there with the slack of probabilities at a code midpoint, as in the small cases)."""
     w = LONG_ROWS_16K if name == LONG_ROWS_16K.name else inputs.WORKLOADS[name]
-    print(f"\n[{name} int8] generating inputs", flush=True)
+    print(f"\n[{name} int8{' fp8' if fp8 else ''}] generating inputs", flush=True)
     q, k, v = inputs.make_inputs(w)
-    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=sale.FLAG_ATTN_INT8_QK)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len,
+                    flags=sale.FLAG_ATTN_INT8_QK | (sale.FLAG_ATTN_FP8_PV if fp8 else 0))
     dev = torch.device("cuda:0")
     qd, kd, vd = (t.unsqueeze(0).to(dev) for t in (q, k, v))
     tau = torch.tensor([w.tau], dtype=torch.float32, device=dev)
@@ -185,6 +189,7 @@ def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
     o_sparse = o_sparse.clone()
     o_dense, _ = sale.dense_attn(p, qd, kd, vd, ws=ws)
     q8, k8, qs8, ks8, mean = sale.attn_int8_operands(p, qd, kd)
+    v_scale = sale.attn_fp8_operands(p, vd)[1] if fp8 else None
     torch.cuda.synchronize()
     print(f"[{name} int8] GPU path done", flush=True)
     geo = so.Geometry(w.seq_len, w.head_dim)
@@ -199,19 +204,34 @@ def test_full_size_sampled_parity_int8_computation_pass(sale, name, n_units):
             np.testing.assert_array_equal(mean[0, g].cpu().numpy().view(np.uint32), omean[0].view(np.uint32))
             np.testing.assert_array_equal(k8[0, g].cpu().numpy(), kc[0])
             np.testing.assert_array_equal(ks8[0, g].cpu().numpy().view(np.uint32), oks[0].view(np.uint32))
-            kq = {g: (kc[0], oks[0], v[g].float().numpy(), omean[0])}
-        kc, oks, vf, kmean = kq[g]
+            v8 = None
+            if fp8:
+                v8 = so.quantize_v_fp8(v[g].float().numpy()[None])
+                np.testing.assert_array_equal(v_scale[0, g].cpu().numpy().view(np.uint32), v8[1][0].view(np.uint32))
+            kq = {g: (kc[0], oks[0], v[g].float().numpy(), omean[0], v8)}
+        kc, oks, vf, kmean, v8 = kq[g]
         rs = slice(i * 64, (i + 1) * 64)
         qc, oqs = so.quantize_blocks(q[h, rs].float().numpy()[None], 64, 127)
         np.testing.assert_array_equal(q8[0, h, rs].cpu().numpy(), qc[0])
         assert qs8[0, h, i].cpu().numpy().view(np.uint32) == oqs[0, 0].view(np.uint32)
         got_row = words_to_bool(mask[0, h, i].cpu().numpy(), p.n_k)
-        ref_s, ref_lse = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, got_row,
-                                                   q_blk=q[h, rs].float().numpy(), k_mean=kmean)
-        ref_d, _ = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, np.arange(geo.n_k) <= i)
-        ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"int8 sparse {name} h{h} i{i}")
-        md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"int8 dense {name} h{h} i{i}")
-        np.testing.assert_allclose(lse[0, h, rs].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
+        if fp8:
+            tol = fp8_arg_tol(oqs[0, 0], oks, w.head_dim)
+            ref_s, ref_lse, o_sl, lse_sl = so.attention_block_int8qk_fp8pv(
+                geo, i, qc[0], oqs[0, 0], kc, oks, v8[0][0], v8[1][0], got_row, q_blk=q[h, rs].float().numpy(), k_mean=kmean,
+                arg_tol=tol)
+            ref_d, _, od_sl, _ = so.attention_block_int8qk_fp8pv(geo, i, qc[0], oqs[0, 0], kc, oks, v8[0][0], v8[1][0],
+                                                                 np.arange(geo.n_k) <= i, arg_tol=tol)
+            ms, _ = check_output_fp8(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, o_sl, f"fp8 sparse {name} h{h} i{i}")
+            md, _ = check_output_fp8(o_dense[0, h, rs].float().cpu().numpy(), ref_d, od_sl, f"fp8 dense {name} h{h} i{i}")
+            check_lse_fp8(lse[0, h, rs].cpu().numpy(), ref_lse, lse_sl, f"fp8 sparse {name} h{h} i{i}")
+        else:
+            ref_s, ref_lse = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, got_row,
+                                                       q_blk=q[h, rs].float().numpy(), k_mean=kmean)
+            ref_d, _ = so.attention_block_int8qk(geo, i, qc[0], oqs[0, 0], kc, oks, vf, np.arange(geo.n_k) <= i)
+            ms, _ = check_output(o_sparse[0, h, rs].float().cpu().numpy(), ref_s, f"int8 sparse {name} h{h} i{i}")
+            md, _ = check_output(o_dense[0, h, rs].float().cpu().numpy(), ref_d, f"int8 dense {name} h{h} i{i}")
+            np.testing.assert_allclose(lse[0, h, rs].cpu().numpy(), ref_lse, rtol=0, atol=LSE_ATOL)
         worst_s, worst_d = max(worst_s, ms), max(worst_d, md)
         print(f"[{name} int8] unit (h={h}, i={i}) kept {int(got_row.sum())}/{i + 1} ok", flush=True)
     print(f"[{name} int8] max abs err sparse {worst_s:.3g} dense {worst_d:.3g}")
