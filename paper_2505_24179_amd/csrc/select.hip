@@ -55,57 +55,65 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
   float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};
   const SeqPos sp = seq_pos(g, u.i);               // (variable-length batches: block indices inside the row's sequence)
   const int j_last = j_last_of(g, sp.il), local = local_of(g, j_last);
-  for (int j = 0; j <= j_last; ++j) {
-    if (!in_sink_local(g, j, j_last, local)) { j = j_last - local; continue; }
-    f32x16 acc[MT][2];
+  // The sink-local blocks of the row, numbered t = 0 ..: the sink blocks that are not local ones, then the local
+  // ones up to the diagonal.  They are swept in half-blocks of 32 keys (hs = t * MT + mt) with the operands of the
+  // next half requested before the current one is multiplied: two register sets that swap roles, the last half
+  // requesting itself again so that every step issues the same loads.
+  const int lo_local = max(j_last - local + 1, 0);
+  const int n_s = min(g.sink_blocks, lo_local);
+  const int n_hs = (n_s + j_last - lo_local + 1) * MT;
+  auto block_of = [&](int hs) { const int t = hs / MT; return t < n_s ? t : lo_local + (t - n_s); };
+  auto fetch = [&](int hs, bf16x8 (&kk)[8]) __attribute__((always_inline)) {
+    const uint16_t* row = k + row_off(g.sk, u.kvh, (sp.kb0 + block_of(hs)) * g.bk + 32 * (hs % MT) + c) + 8 * h;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int s = 0; s < 8; ++s) kk[s] = *(const bf16x8*)(row + 16 * s);
+  };
+  const float kLog2e = 1.4426950408889634f;
+  auto half = [&](int hs, const bf16x8 (&kk)[8], bf16x8 (&kn)[8]) __attribute__((always_inline)) {
+    fetch(min(hs + 1, n_hs - 1), kn);
+    f32x16 acc[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nt][r] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[s], qf[0][s], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kk[s], qf[1][s], acc[1], 0, 0, 0);
+    }
+    const int j = block_of(hs), mt = hs % MT;
+    // keys of this half that lie after a query row (only with SALE_FLAG_STATS_CAUSAL)
+    const int ahead = j * g.bk + 32 * mt - sp.il * 64;      // first key of the half minus first query row
+    if (g.stats_causal && ahead + 31 > 0) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const uint16_t* row = k + row_off(g.sk, u.kvh, (sp.kb0 + j) * g.bk + 32 * mt + c) + 8 * h;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 a = *(const bf16x8*)(row + 16 * s);
-        acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][s], acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][s], acc[mt][1], 0, 0, 0);
-      }
+        for (int r = 0; r < 16; ++r)
+          if (ahead + mfma32_row(r, lane) > 32 * nt + c) acc[nt][r] = -INFINITY;
     }
-    // keys of this block that lie after a query row (only with SALE_FLAG_STATS_CAUSAL)
-    const bool mask_diag = g.stats_causal && (j + 1) * g.bk - 1 > sp.il * 64;
-    const int ahead = j * g.bk - sp.il * 64;      // first key of the block minus first query row
     // (VALU-bound: per score one half of a v_max3, one FMA that folds 1 / sqrt(d), log2(e) and the maximum,
-    // one v_exp_f32 and one add; the causal select only where a block needs it)
-    if (mask_diag) {
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (ahead > (32 * nt + c) - (32 * mt + mfma32_row(r, lane))) acc[mt][nt][r] = -INFINITY;
-    }
-    const float kLog2e = 1.4426950408889634f;
+    // one v_exp_f32 and one add)
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      float mx = -INFINITY;
+      float mx = fmaxf(acc[nt][0], acc[nt][1]);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) mx = fmaxf(fmaxf(mx, acc[mt][nt][r]), acc[mt][nt][r + 1]);
+      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, acc[nt][r]), acc[nt][r + 1]);
       const float m_new = fmaxf(m[nt], mx * rsd);      // rsd > 0: the maximum of the products is the product of the maximum
       const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
       const float mb = m_safe * kLog2e;
       float sum = 0.0f;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mt][nt][r], rsd * kLog2e, -mb));
+      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[nt][r], rsd * kLog2e, -mb));
       l[nt] = l[nt] * __builtin_amdgcn_exp2f(m[nt] * kLog2e - mb) + sum;
       m[nt] = m_new;
+    }
+  };
+  {
+    bf16x8 ka[8], kb[8];
+    fetch(0, ka);                                   // (n_hs >= 1: the diagonal block is always local)
+    for (int hs = 0; hs < n_hs; hs += 2) {
+      half(hs, ka, kb);
+      if (hs + 1 < n_hs) half(hs + 1, kb, ka);
     }
   }
 #pragma unroll
@@ -229,7 +237,7 @@ __device__ __forceinline__ float lane_max(const f32x16 acc[MT][2], int nt) {
 }
 
 // One wave scores HPW query heads of one GQA group at the same query block, so every K~ fragment it
-// loads feeds HPW x 2 MFMAs (HPW = 4 when the group allows: 14.6 against 15.3 ms at 128K with 64-key blocks).  A workgroup is 4 such waves (consecutive head sets / query blocks of one
+// loads feeds HPW x 2 MFMAs (HPW = 4 when the group allows).  A workgroup is 4 such waves (consecutive head sets / query blocks of one
 // KV head); workgroups go round-robin over KV heads, longest rows first.
 // (At least 2 waves per SIMD caps the register file at 256 VGPRs, which lets the MFMA results land in
 // ordinary VGPRs instead of AGPRs that the max chain would have to copy out one by one.)
@@ -264,40 +272,68 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
 
   const SeqPos sp = seq_pos(g, i);
   const int j_last = j_last_of(g, sp.il), local = local_of(g, j_last);
+  const int mid_lo = g.sink_blocks, mid_hi = j_last - local;      // the middle blocks (inclusive), scored below
   int count[HPW];
-#pragma unroll
-  for (int a = 0; a < HPW; ++a) count[a] = 0;
-  for (int wc = 0; wc < g.words; ++wc) {
-    uint64_t word[HPW];
-#pragma unroll
-    for (int a = 0; a < HPW; ++a) word[a] = 0;
-    const int j_end = min(64, j_last + 1 - wc * 64);
-    for (int jj = 0; jj < j_end; ++jj) {
-      const int j = wc * 64 + jj;
-      if (in_sink_local(g, j, j_last, local)) {
-#pragma unroll
-        for (int a = 0; a < HPW; ++a) word[a] |= 1ull << jj;
-        continue;
-      }
-      i32x8 kf[MT][2];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) load_x6(k6, kgrp0 + (size_t)(sp.kb0 + j) * MT + mt, lane, kf[mt]);
-      const float sk = ks[sp.kb0 + j];
-#pragma unroll
-      for (int a = 0; a < HPW; ++a) {
-        f32x16 acc[MT][2];
-        qk_tile_fp6<MT>(kf, qf[a], acc);
-        const float cj = cq[a] * sk;
-        const bool pass = (lane_max<MT>(acc, 0) * cj >= th[a][0]) || (lane_max<MT>(acc, 1) * cj >= th[a][1]);
-        word[a] |= (uint64_t)(__ballot(pass) != 0ull) << jj;
-      }
-    }
+  uint64_t word[HPW];
+  int wc = 0;                                                       // mask word being assembled
+  // Bits of word wc that are set without scoring: the sink and local blocks the row can see.
+  auto fixed_bits = [&]() -> uint64_t {
+    auto span = [&](int lo, int hi) -> uint64_t {                   // bits of blocks lo..hi that fall into word wc
+      lo = max(lo - wc * 64, 0); hi = min(hi - wc * 64, 63);
+      return lo > hi ? 0ull : ((~0ull >> (63 - hi)) & (~0ull << lo));
+    };
+    return span(0, min(g.sink_blocks - 1, j_last)) | span(max(mid_hi + 1, 0), j_last);
+  };
+  // Completes word wc (store, count) and starts the next one.
+  auto flush = [&]() {
 #pragma unroll
     for (int a = 0; a < HPW; ++a) {
       if (lane == 0) mask[((size_t)(qh0 + a) * g.n_qb + i) * g.words + wc] = word[a];
       count[a] += __popcll(word[a]);
     }
+    ++wc;
+    const uint64_t fb = fixed_bits();
+#pragma unroll
+    for (int a = 0; a < HPW; ++a) word[a] = fb;
+  };
+  {
+    const uint64_t fb = fixed_bits();
+#pragma unroll
+    for (int a = 0; a < HPW; ++a) { count[a] = 0; word[a] = fb; }
   }
+  // The operands of a key block are requested one block ahead (two register sets that swap roles): the loads of
+  // block j + 1 are in flight while block j is scored.  The last block requests itself again, so every step
+  // issues the same loads and the wait counts stay exact.
+  i32x8 kfa[MT][2], kfb[MT][2];
+  float ska = 0.0f, skb = 0.0f;
+  auto fetch = [&](int j, i32x8 (&kf)[MT][2], float& sk) __attribute__((always_inline)) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) load_x6(k6, kgrp0 + (size_t)(sp.kb0 + j) * MT + mt, lane, kf[mt]);
+    sk = ks[sp.kb0 + j];
+  };
+  auto score = [&](int j, const i32x8 (&kf)[MT][2], float sk, i32x8 (&kn)[MT][2], float& skn) __attribute__((always_inline)) {
+    fetch(min(j + 1, mid_hi), kn, skn);
+    while (wc < (j >> 6)) flush();
+#pragma unroll
+    for (int a = 0; a < HPW; ++a) {
+      f32x16 acc[MT][2];
+      qk_tile_fp6<MT>(kf, qf[a], acc);
+      const float cj = cq[a] * sk;
+      // (both halves always: a short-circuit would put the second maximum chain behind a branch, where it
+      // cannot be interleaved with the next head's MFMAs; most blocks fail the first test anyway)
+      const bool p0 = lane_max<MT>(acc, 0) * cj >= th[a][0];
+      const bool p1 = lane_max<MT>(acc, 1) * cj >= th[a][1];
+      word[a] |= (uint64_t)(__ballot(p0 | p1) != 0ull) << (j & 63);
+    }
+  };
+  if (mid_lo <= mid_hi) {
+    fetch(mid_lo, kfa, ska);
+    for (int j = mid_lo; j <= mid_hi; j += 2) {
+      score(j, kfa, ska, kfb, skb);
+      if (j + 1 <= mid_hi) score(j + 1, kfb, skb, kfa, ska);
+    }
+  }
+  while (wc < g.words) flush();
 #pragma unroll
   for (int a = 0; a < HPW; ++a)
     if (lane == 0) row_counts[(size_t)(qh0 + a) * g.n_qb + i] = count[a];
