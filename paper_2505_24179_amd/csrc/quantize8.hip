@@ -23,14 +23,28 @@ __global__ __launch_bounds__(256) void ksum_kernel(const uint16_t* __restrict__ 
   if (phase == 0) partial[(size_t)blockIdx.x * 128 + c] = s + other[c];
 }
 
-// mean[kvh][c] = fp32(sum over the head's tiles / N).  One workgroup per KV head.
-__global__ __launch_bounds__(128) void kmean_kernel(const double* __restrict__ partial, int tiles, int seq,
-                                                    float* __restrict__ mean) {
-  const int c = threadIdx.x;
+// mean[kvh][c] = fp32(sum over the head's tiles / N).  One workgroup of 1024 threads per KV head: 8 threads per
+// channel take every 8th tile each, four loads in flight, and meet in LDS.  (The partial sums are fp64 sums of
+// bf16 values: exact for any data whose exponents span less than 53 - 8 - log2(N) bits, so the order is free.)
+__global__ __launch_bounds__(1024) void kmean_kernel(const double* __restrict__ partial, int tiles, int seq,
+                                                     float* __restrict__ mean) {
+  __shared__ double part[8][128];
+  const int c = threadIdx.x & 127, ph = threadIdx.x >> 7;
   const double* p = partial + (size_t)blockIdx.x * tiles * 128 + c;
-  double s = 0.0;
-  for (int t = 0; t < tiles; ++t) s += p[(size_t)t * 128];
-  mean[blockIdx.x * 128 + c] = (float)(s / (double)seq);
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+  int t = ph;
+  for (; t + 24 < tiles; t += 32) {
+    s0 += p[(size_t)t * 128]; s1 += p[(size_t)(t + 8) * 128]; s2 += p[(size_t)(t + 16) * 128]; s3 += p[(size_t)(t + 24) * 128];
+  }
+  for (; t < tiles; t += 8) s0 += p[(size_t)t * 128];
+  part[ph][c] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (ph == 0) {
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += part[i][c];
+    mean[blockIdx.x * 128 + c] = (float)(s / (double)seq);
+  }
 }
 
 // One workgroup per (head, 64-row block).  Thread t holds 32 channels (32 (t % 4) ..) of row t / 4.
@@ -116,16 +130,30 @@ __global__ __launch_bounds__(256) void vamax_kernel(const uint16_t* __restrict__
   if (phase == 0) partial[(size_t)blockIdx.x * 128 + c] = fmaxf(m, other[c]);
 }
 
-// Per KV head: scale[c] = amax / 448 and inv[c] = 448 / amax (1 and 0 for an all-zero channel).
-__global__ __launch_bounds__(128) void vscale_kernel(const float* __restrict__ partial, int tiles, float* __restrict__ scale,
-                                                     float* __restrict__ inv) {
-  const int c = threadIdx.x;
+// Per KV head: scale[c] = amax / 448 and inv[c] = 448 / amax (1 and 0 for an all-zero channel).  1024 threads as
+// in kmean_kernel.
+__global__ __launch_bounds__(1024) void vscale_kernel(const float* __restrict__ partial, int tiles, float* __restrict__ scale,
+                                                      float* __restrict__ inv) {
+  __shared__ float part[8][128];
+  const int c = threadIdx.x & 127, ph = threadIdx.x >> 7;
   const float* p = partial + (size_t)blockIdx.x * tiles * 128 + c;
-  float amax = 0.0f;
-  for (int t = 0; t < tiles; ++t) amax = fmaxf(amax, p[(size_t)t * 128]);
-  const bool zero = amax == 0.0f;
-  scale[blockIdx.x * 128 + c] = zero ? 1.0f : amax / 448.0f;
-  inv[blockIdx.x * 128 + c] = zero ? 0.0f : 448.0f / amax;
+  float m0 = 0.0f, m1 = 0.0f, m2 = 0.0f, m3 = 0.0f;
+  int t = ph;
+  for (; t + 24 < tiles; t += 32) {
+    m0 = fmaxf(m0, p[(size_t)t * 128]); m1 = fmaxf(m1, p[(size_t)(t + 8) * 128]);
+    m2 = fmaxf(m2, p[(size_t)(t + 16) * 128]); m3 = fmaxf(m3, p[(size_t)(t + 24) * 128]);
+  }
+  for (; t < tiles; t += 8) m0 = fmaxf(m0, p[(size_t)t * 128]);
+  part[ph][c] = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+  __syncthreads();
+  if (ph == 0) {
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, part[i][c]);
+    const bool zero = amax == 0.0f;
+    scale[blockIdx.x * 128 + c] = zero ? 1.0f : amax / 448.0f;
+    inv[blockIdx.x * 128 + c] = zero ? 0.0f : 448.0f / amax;
+  }
 }
 
 __device__ __forceinline__ uint32_t fp8x4(float a, float b, float c, float d) {
@@ -214,7 +242,7 @@ int launch_fp8_operands(const sale_params_t* p, const void* v, const Fp8Operands
   const Geo g = make_geo(p);
   vamax_kernel<<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)v, g.sv, tiles, w.partial);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  vscale_kernel<<<dim3((unsigned)n_kvh), dim3(128), 0, st>>>(w.partial, tiles, w.v_scale, w.v_inv);
+  vscale_kernel<<<dim3((unsigned)n_kvh), dim3(1024), 0, st>>>(w.partial, tiles, w.v_scale, w.v_inv);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   if (frag)
     quantize_v8_kernel<true><<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)v, g.sv, tiles, w.v_inv, w.v8);
@@ -252,7 +280,7 @@ int launch_int8_operands(const sale_params_t* p, const void* q, const void* k, c
   const Geo g = make_geo(p);
   ksum_kernel<<<dim3((unsigned)(n_kvh * tiles)), dim3(256), 0, st>>>((const uint16_t*)k, g.sk, tiles, w.partial);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  kmean_kernel<<<dim3((unsigned)n_kvh), dim3(128), 0, st>>>(w.partial, tiles, p->seq_len, w.k_mean);
+  kmean_kernel<<<dim3((unsigned)n_kvh), dim3(1024), 0, st>>>(w.partial, tiles, p->seq_len, w.k_mean);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   quantize8_kernel<false><<<dim3((unsigned)(n_qh * tiles)), dim3(256), 0, st>>>((const uint16_t*)q, g.sq, nullptr, tiles,
                                                                                w.q8, w.q_scale);
