@@ -133,7 +133,15 @@ def main() -> int:
         counts = torch.empty(1, w.n_q_heads, p.n_q, dtype=torch.int32, device=dev)
         o = torch.empty_like(qd)
         ws_sel = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SELECT)), dtype=torch.uint8, device=dev)
-        ws_att = torch.empty(max(1, sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)), dtype=torch.uint8, device=dev)
+        # The attention workspace holds one parking slot per LONG row (rows keeping more than 192 x 64 keys are swept
+        # window by window): their number is read once from a first Selection-Pass, outside the timed region.
+        sale.quantize_qk(p, qd, kd, out=(q4, k4, qs, ks))
+        sale.select(p, qd, kd, q4, k4, qs, ks, tau, out=(mask, counts), ws=ws_sel)
+        n_long = int((counts > 192 * (64 // args.block_k)).sum().item())
+        ws_bytes = {"select": int(ws_sel.numel()),
+                    "sparse_attn": sale.workspace_bytes(p, sale.WS_SPARSE_ATTN_MIN) + n_long * sale.PARKED_ROW_BYTES,
+                    "dense_attn": sale.workspace_bytes(p, sale.WS_DENSE_ATTN), "long_rows": n_long}
+        ws_att = torch.empty(max(1, ws_bytes["sparse_attn"], ws_bytes["dense_attn"]), dtype=torch.uint8, device=dev)
 
         def step(ev=None):
             if ev: ev[0].record()
@@ -198,7 +206,7 @@ def main() -> int:
         fig = {
             "sale_ms": sale_ms, "wall_ms": wall_ms, "input_gen_s": t_gen,
             "stages_ms": {"quantize": quant_ms, "select": select_ms, "sparse_attn": sparse_ms, "dense_attn": dense_ms},
-            "density": kept_pairs / causal_pairs,
+            "density": kept_pairs / causal_pairs, "workspace_bytes": ws_bytes,
             "select_overhead_pct": None if not dense_ms else 100.0 * (quant_ms + select_ms) / dense_ms,
             "select_overhead_pct_of_dense_at_60pct_peak": 100.0 * (quant_ms + select_ms) / dense60_ms,
             "computation_pass_speedup": None if not dense_ms else dense_ms / sparse_ms,
@@ -258,6 +266,7 @@ def main() -> int:
                    "seed": w.seed},
         "stages_ms": fig["stages_ms"],
         "density": fig["density"],
+        "workspace_bytes": fig["workspace_bytes"],
         "select_overhead_pct": fig["select_overhead_pct"],
         "select_overhead_pct_of_dense_at_60pct_peak": fig["select_overhead_pct_of_dense_at_60pct_peak"],
         "computation_pass_speedup": fig["computation_pass_speedup"],

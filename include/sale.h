@@ -139,6 +139,9 @@ typedef struct sale_params {
 #define SALE_WS_CALIBRATE 4
 #define SALE_WS_INT8_OPERANDS 5
 #define SALE_WS_FP8_OPERANDS 6
+/* sale_sparse_attn without parking slots (see there); one slot more per SALE_PARKED_ROW_BYTES. */
+#define SALE_WS_SPARSE_ATTN_MIN 7
+#define SALE_PARKED_ROW_BYTES 33792u
 
 /* Bytes of workspace `which_call` needs for `p` (0 if the call needs none or the
  * parameters are invalid). */
@@ -242,9 +245,18 @@ int sale_select_static(const sale_params_t* p, const void* q, const void* k,
  *                   SALE_FLAG_ATTN_INT8_QK the logits are the 8-bit estimates;
  *                   the per-row shift q_r . k_mean / sqrt(d) that the K smoothing
  *                   takes out is added back, so lse still refers to S above.
- *   ws            : workspace of sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN) bytes
- *                   (K and V are copied into it once per call in the kernel's
- *                   operand order; 2 * sizeof(K) bytes)
+ *   ws            : workspace (K and V are copied into it once per call in the
+ *                   kernel's operand order, 2 * sizeof(K) bytes; tables; then parking
+ *                   slots).  Any ws_bytes >= sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN_MIN)
+ *                   is accepted.  Above 16K tokens, rows keeping more than 192 x 64 keys
+ *                   are swept window by window (so that a window of K, V stays in L2)
+ *                   with their accumulators parked in a slot of SALE_PARKED_ROW_BYTES
+ *                   in between; the slots are what lies beyond the MIN size.  A long
+ *                   row that finds no slot is swept in one go instead: the same result
+ *                   bit for bit, slower.  SALE_WS_SPARSE_ATTN is the size with one slot
+ *                   per 64-row block (never short of slots); a caller that knows how
+ *                   many rows of row_counts exceed 192 x (64 / block_k) passes
+ *                   MIN + that many * SALE_PARKED_ROW_BYTES.
  */
 int sale_sparse_attn(const sale_params_t* p, const void* q, const void* k, const void* v,
                      const uint64_t* block_mask, const int32_t* row_counts,

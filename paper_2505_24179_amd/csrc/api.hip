@@ -136,15 +136,14 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
       // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copies of Q~ and K~ (96 B per row)
       return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96 + seq_table_bytes(p);
     case SALE_WS_SPARSE_ATTN:
-    case SALE_WS_DENSE_ATTN:
-      // K and V copied once into MFMA fragment order, parked row state (fp32 O^T accumulators and
-      // max / sum per lane: 33 KB per 64-row block), the order in which rows are issued and the tables (one
-      // per window launch, at most 32) that balance them over the XCDs
-      // (+ the 8-bit operand copies of the quantized Computation-Pass)
-      return 2 * (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t) +
-             (rows / kBlockQ) * ((1 + kMaskWordsMax / 2) * sizeof(int32_t) + 2048 * 16 + 256 * 4) + (128u << 10) + 16 +
-             ((p->flags & SALE_FLAG_ATTN_INT8_QK) ? int8_operand_bytes(p) : 0) +
-             ((p->flags & SALE_FLAG_ATTN_FP8_PV) ? fp8_operand_bytes(p) : 0) + seq_table_bytes(p);
+      // K and V copied once into MFMA fragment order, the order in which rows are issued, the tables (one per
+      // window launch, at most 32) that balance them over the XCDs, the 8-bit operand copies of the quantized
+      // Computation-Pass - and one parking slot (fp32 O^T accumulators and max / sum per lane: 33 KB) per 64-row block
+      return attn_fixed_bytes(p, true) + (rows / kBlockQ) * kParkedRowBytes;
+    case SALE_WS_SPARSE_ATTN_MIN:      // the same without parking slots
+      return attn_fixed_bytes(p, true);
+    case SALE_WS_DENSE_ATTN:           // K', V' (+ the 8-bit operand copies)
+      return attn_fixed_bytes(p, false);
     case SALE_WS_CALIBRATE:
       return calibrate_workspace_bytes(p);
     case SALE_WS_INT8_OPERANDS:

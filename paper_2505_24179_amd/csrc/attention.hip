@@ -61,9 +61,11 @@ namespace sale {
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16_t* __restrict__ k, Strided lk,
                                                            const uint16_t* __restrict__ v, Strided lv,
-                                                           u32x4* __restrict__ kp, u32x4* __restrict__ vp) {
+                                                           u32x4* __restrict__ kp, u32x4* __restrict__ vp,
+                                                           int* __restrict__ slot_counter) {
   __shared__ uint16_t sv[64 * (kHeadDim + 2)];
   const int tid = threadIdx.x;
+  if (slot_counter && blockIdx.x == 0 && tid == 0) *slot_counter = 0;      // (for order_units_kernel, next on the stream)
   const size_t tile = blockIdx.x;                      // flattened (kv head, block j): rows tile*64 .. +63
   const int tiles_per_head = seq / 64;
   const uint16_t* kt = k + row_off(lk, (int)(tile / tiles_per_head), (int)(tile % tiles_per_head) * 64);
@@ -101,18 +103,18 @@ __global__ __launch_bounds__(256) void rearrange_kv_kernel(int seq, const uint16
   }
 }
 
-// Which rows a launch handles and which part of them.  Rows whose kept-block count lies in
-// [count_min, count_max] take part (counts == nullptr: all rows).  win_word < 0: the whole row in one go.
+// Which rows a launch handles and which part of them.  win_word < 0: the whole row in one go.
 // win_word >= 0: only the key blocks of that 64-block mask word; a row then resumes from the state
 // (fp32 O^T accumulators, running max and sum, exactly the register contents) that the launch of the
-// previous word parked in the workspace, and parks it again unless this word holds its diagonal block.
+// previous word parked in its slot of the workspace, and parks it again unless this word holds its diagonal block.
+// slot_of (window launches): the parking slot of every row block, or -1 for the rows that are swept whole: the
+// short ones, and the long ones that found no slot in the caller's workspace.
 // Workgroups from number tail_from on (tail_from >= 0) form the tail of a window launch: they take the
-// rows the windows leave out (count <= count_max), whole, rank tail_phase + k * tail_stride of each KV head's
+// rows without a slot, whole, rank tail_phase + k * tail_stride of each KV head's
 // sorted list, so that every window launch ends with its share of short rows and its last long rows do
 // not leave the chip idle.
 struct RowFilter {
-  const int32_t* counts;
-  int count_min, count_max;
+  const int32_t* slot_of;
   int win_word;    // first mask word of the window, or < 0
   int win_words;   // words per window
   int tail_from, tail_stride, tail_phase;
@@ -171,10 +173,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   }
   if (!u.valid) return;
   const size_t unit_flat = (size_t)u.qh * g.n_qb + u.i;
-  if (flt.counts && (tail || flt.tail_from < 0)) {
-    const int cnt = flt.counts[unit_flat];
-    if (cnt < flt.count_min || cnt > flt.count_max) return;
-  }
+  const int slot = flt.slot_of ? flt.slot_of[unit_flat] : -1;
+  if (tail && slot >= 0) return;      // (rows with a slot are swept window by window through the tables)
 
   // ---- this wave's list of kept blocks: the set bits of its mask row, below the diagonal ----
   const uint64_t* mrow = mask ? mask + ((size_t)u.qh * g.n_qb + u.i) * g.words : nullptr;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};      // m_run in log2 units
 
   if (resume) {
-    const f32x4* so = st_o + unit_flat * 2048 + lane;       // [dt][nt][quarter][lane] 16-byte chunks
+    const f32x4* so = st_o + (size_t)slot * 2048 + lane;       // [dt][nt][quarter][lane] 16-byte chunks
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 #pragma unroll
           for (int e = 0; e < 4; ++e) oacc[dt][nt][4 * qd + e] = w[e];
         }
-    const float* sml = st_ml + unit_flat * 256 + lane;       // [m nt0, m nt1, l nt0, l nt1][lane]
+    const float* sml = st_ml + (size_t)slot * 256 + lane;       // [m nt0, m nt1, l nt0, l nt1][lane]
     m_run[0] = sml[0]; m_run[1] = sml[64]; l_run[0] = sml[128]; l_run[1] = sml[192];
   }
   int wc_it = word_lo;
@@ -661,7 +661,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
   }
 
   if (park) {
-    f32x4* so = st_o + unit_flat * 2048 + lane;
+    f32x4* so = st_o + (size_t)slot * 2048 + lane;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -673,7 +673,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
           for (int e = 0; e < 4; ++e) w[e] = oacc[dt][nt][4 * qd + e];
           so[((dt * 2 + nt) * 4 + qd) * 64] = w;
         }
-    float* sml = st_ml + unit_flat * 256 + lane;
+    float* sml = st_ml + (size_t)slot * 256 + lane;
     sml[0] = m_run[0]; sml[64] = m_run[1]; sml[128] = l_run[0]; sml[192] = l_run[1];
     return;
   }
@@ -743,8 +743,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_rows_kernel(Geo g, const uint
 
 // Counting sort of the units of each KV head by kept-block count, descending:
 // order[kvh][rank] = unit id (block * group + head-in-group).  One workgroup per KV head.
+// slot_of (optional): rows keeping more than long_count blocks draw a parking slot from *slot_counter (cleared by
+// the K' / V' copy that precedes this kernel) as long as there are slots; every other row gets -1.
 __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t* __restrict__ row_counts,
-                                                           int32_t* __restrict__ order) {
+                                                           int32_t* __restrict__ order, int32_t* __restrict__ slot_of,
+                                                           int long_count, int n_slots, int* __restrict__ slot_counter) {
   __shared__ int bin[kMaskWordsMax * 64 + 2];
   const int kvh = blockIdx.x, units = g.n_qb * g.group;
   const int max_count = min(g.n_kb, g.words * 64);      // (a row keeps at most the key blocks of its own sequence)
@@ -762,8 +765,18 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
     for (int b = nbins - 1; b >= 0; --b) { const int n = bin[b]; bin[b] = run; run += n; }
   }
   __syncthreads();
-  for (int id = threadIdx.x; id < units; id += blockDim.x)
-    order[(size_t)kvh * units + atomicAdd(&bin[count_of(id)], 1)] = id;
+  for (int id = threadIdx.x; id < units; id += blockDim.x) {
+    const int cnt = count_of(id);
+    order[(size_t)kvh * units + atomicAdd(&bin[cnt], 1)] = id;
+    if (slot_of) {
+      int slot = -1;
+      if (cnt > long_count && n_slots > 0) {
+        slot = atomicAdd(slot_counter, 1);
+        if (slot >= n_slots) slot = -1;
+      }
+      slot_of[(size_t)(kvh * g.group + id % g.group) * g.n_qb + id / g.group] = slot;
+    }
+  }
 }
 
 // All three in units of 64 keys (scaled by 64 / b_k for a mask with one bit per b_k keys).
@@ -774,7 +787,7 @@ __global__ __launch_bounds__(1024) void order_units_kernel(Geo g, const int32_t*
 // so-many-th of the sorted list) of the units of every over-loaded head to the lanes of the under-loaded
 // ones, in proportion to the work they lack in THAT window:
 //   assign[window][lane][slot] = kvh * units + unit id, or -1.
-// A unit takes part in a window if its row is long (count > min_count) and keeps a block there, or if the
+// A unit takes part in a window if its row has a parking slot (a long row) and keeps a block there, or if the
 // window holds its diagonal block (where the row is finished whatever it keeps).
 // Falls back to lane = KV head when there are too many lanes or a lane would overflow.
 constexpr int kMaxLanes = 256;
@@ -786,14 +799,14 @@ constexpr size_t kLaneLoadBytes = (size_t)(kMaskWordsMax / 2) * kMaxLanes * size
 struct WindowScan {
   const Geo& g;
   const uint64_t* mask;
-  const int32_t* row_counts;
+  const int32_t* slot_of;
   const int32_t* order;
-  int min_count, w0, w1, bits_per_q, units;
+  int w0, w1, bits_per_q, units;
   // blocks the unit at rank r of head h keeps in this window (-1: it does not take part)
   __device__ int in_window(int h, int r, int& id) const {
     id = order[(size_t)h * units + r];
     const int i = id / g.group, qh = h * g.group + id % g.group;
-    if (row_counts[(size_t)qh * g.n_qb + i] <= min_count) return -1;
+    if (slot_of[(size_t)qh * g.n_qb + i] < 0) return -1;      // swept whole, in a tail
     const int j_last = (seq_pos(g, i).il + 1) * bits_per_q - 1, last_word = j_last >> 6;
     if (w0 > last_word) return -1;
     const uint64_t* mrow = mask + ((size_t)qh * g.n_qb + i) * g.words;
@@ -833,8 +846,8 @@ __device__ __forceinline__ int block_scan_1024(int v, int* wave_sum, int& sum) {
 // Workgroup (window, head): number of participating units and their work in the window; clears the head's
 // own lane of the window's table.
 __global__ __launch_bounds__(1024) void window_load_kernel(Geo g, const uint64_t* __restrict__ mask,
-                                                           const int32_t* __restrict__ row_counts,
-                                                           const int32_t* __restrict__ order, int min_count, int win_words,
+                                                           const int32_t* __restrict__ slot_of,
+                                                           const int32_t* __restrict__ order, int win_words,
                                                            int bits_per_q, LaneLoad* __restrict__ load,
                                                            int32_t* __restrict__ assign_all) {
   __shared__ int wave_sum[16];
@@ -842,7 +855,7 @@ __global__ __launch_bounds__(1024) void window_load_kernel(Geo g, const uint64_t
   const int units = g.n_qb * g.group, lanes = g.n_kvh;
   const int win = blockIdx.x / lanes, h = blockIdx.x % lanes;
   const int tid = threadIdx.x, per = (units + 1023) / 1024;
-  const WindowScan ws = {g, mask, row_counts, order, min_count, win * win_words, (win + 1) * win_words, bits_per_q, units};
+  const WindowScan ws = {g, mask, slot_of, order, win * win_words, (win + 1) * win_words, bits_per_q, units};
   int32_t* mine = assign_all + ((size_t)win * lanes + h) * units;
   for (int e = tid; e < units; e += 1024) mine[e] = -1;
   if (tid == 0) work = 0;
@@ -862,8 +875,8 @@ __global__ __launch_bounds__(1024) void window_load_kernel(Geo g, const uint64_t
 
 // Workgroup (window, head): places the head's participating units in the window's table.
 __global__ __launch_bounds__(1024) void balance_kernel(Geo g, const uint64_t* __restrict__ mask,
-                                                       const int32_t* __restrict__ row_counts,
-                                                       const int32_t* __restrict__ order, int min_count, int win_words,
+                                                       const int32_t* __restrict__ slot_of,
+                                                       const int32_t* __restrict__ order, int win_words,
                                                        int bits_per_q, const LaneLoad* __restrict__ load,
                                                        int32_t* __restrict__ assign_all) {
   __shared__ int n_shed_h, shed_off_h, n_in_h, recv_lo[kMaxLanes + 1];
@@ -871,7 +884,7 @@ __global__ __launch_bounds__(1024) void balance_kernel(Geo g, const uint64_t* __
   const int units = g.n_qb * g.group, lanes = g.n_kvh;
   const int win = blockIdx.x / lanes, h = blockIdx.x % lanes;
   const int tid = threadIdx.x, per = (units + 1023) / 1024;
-  const WindowScan ws = {g, mask, row_counts, order, min_count, win * win_words, (win + 1) * win_words, bits_per_q, units};
+  const WindowScan ws = {g, mask, slot_of, order, win * win_words, (win + 1) * win_words, bits_per_q, units};
   int32_t* assign = assign_all + (size_t)win * lanes * units;
   const bool balance = lanes <= kMaxLanes && lanes > 1;
   if (tid == 0) {
@@ -949,17 +962,21 @@ namespace {
 
 template <bool BK32, bool QK8, bool PV8 = false>
 int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const bf16x8* vp, Qk8 q8o, const uint64_t* mask,
-                       const int32_t* row_counts, int32_t* order, int32_t* assign, uint16_t* o, float* o32, float* lse,
-                       f32x4* st_o, float* st_ml, hipStream_t st) {
+                       const int32_t* row_counts, int32_t* order, int32_t* assign, LaneLoad* load, int32_t* slot_of,
+                       int* slot_counter, int n_slots, uint16_t* o, float* o32, float* lse, f32x4* st_o, float* st_ml,
+                       hipStream_t st) {
   const int units = g.n_qb * g.group;
   const int f = BK32 ? 2 : 1;          // mask bits per 64 keys
   const dim3 grid((unsigned)(units * g.n_kvh));
-  const RowFilter all = {nullptr, 0, 0, -1, 0, -1, 0, 0};
+  const RowFilter all = {nullptr, -1, 0, -1, 0, 0};
+  // Without a single parking slot in the workspace every row is swept whole.
+  const bool windows = row_counts && g.words > kWindowMinWords * f && n_slots > 0;
   if (row_counts) {
-    order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order);
+    order_units_kernel<<<dim3((unsigned)g.n_kvh), dim3(1024), 0, st>>>(g, row_counts, order, windows ? slot_of : nullptr,
+                                                                       kLongRow * f, n_slots, slot_counter);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
-  if (!row_counts || g.words <= kWindowMinWords * f) {
+  if (!windows) {
     // (one sweep per row: every row reads K', V' of the whole sequence, and moving rows to another XCD costs
     // more L2 misses than the balance gains: 3.1 against 2.7 ms at 32K)
     attn_rows_kernel<1, BK32, QK8, PV8><<<grid, dim3(64), 0, st>>>(g, q, kp, vp, q8o, mask, row_counts ? order : nullptr, nullptr,
@@ -980,16 +997,14 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
   // KV head's sorted list (the tail of the grid), which fill the chip while its last long rows finish.
   const int step = kWindowWords * f, launches = (g.words + step - 1) / step;
   const int tail_wgs = ((units + launches - 1) / launches) * g.n_kvh;
-  LaneLoad* load = (LaneLoad*)(((uintptr_t)(assign + (size_t)(kMaskWordsMax / 2) * grid.x) + 15) & ~(uintptr_t)15);
-  window_load_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, row_counts, order, kLongRow * f,
-                                                                                 step, f, load, assign);
+  window_load_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, slot_of, order, step, f, load,
+                                                                                 assign);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
-  balance_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, row_counts, order, kLongRow * f, step,
-                                                                             f, load, assign);
+  balance_kernel<<<dim3((unsigned)(launches * g.n_kvh)), dim3(1024), 0, st>>>(g, mask, slot_of, order, step, f, load, assign);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   for (int n = 0; n < launches; ++n) {
-    // (the table holds the long rows only; the count filter applies to the tail)
-    const RowFilter flt = {row_counts, -0x7FFFFFFF, kLongRow * f, n * step, step, (int)grid.x, launches, n};
+    // (the table holds the rows with a parking slot; the tail takes the others)
+    const RowFilter flt = {slot_of, n * step, step, (int)grid.x, launches, n};
     attn_rows_kernel<1, BK32, QK8, PV8><<<dim3(grid.x + (unsigned)tail_wgs), dim3(64), 0, st>>>(
         g, q, kp, vp, q8o, mask, order, assign + (size_t)n * grid.x, o, o32, lse, flt, st_o, st_ml);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
@@ -999,44 +1014,79 @@ int launch_sparse_rows(const Geo& g, const uint16_t* q, const bf16x8* kp, const 
 
 }  // namespace
 
-// o: bf16 output, or (o32 != nullptr) fp32 output instead.  mask == nullptr: dense causal attention
-// (independent of b_k).
-int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
-                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st) {
-  Geo g = make_geo(p);
-  if (p->n_seqs > 0) {      // the per-block sequence table is the last part of the workspace
-    const int which = mask ? SALE_WS_SPARSE_ATTN : SALE_WS_DENSE_ATTN;
-    int32_t* table = (int32_t*)((uint8_t*)ws + sale_workspace_bytes(p, which) - seq_table_bytes(p));
-    const int rc = build_seq_table(p, table, st);
-    if (rc != SALE_OK) return rc;
-    g.seq_start = table;
+// Workspace of the attention calls.  Fixed part: K' | V' | (sparse: unit order | parking slot per row block | balanced
+// issue tables, room for 32 window launches | per-window head loads | slot counter) | 8-bit operand copies | FP8 copy
+// of V | per-block sequence table; then (sparse) the parking slots, 33 KB each: as many as the caller's workspace holds.
+namespace {
+struct AttnWs {
+  u32x4 *kp, *vp;
+  int32_t *order, *slot_of, *assign;
+  LaneLoad* load;
+  int* slot_counter;
+  uint8_t *ops8, *ops_fp8;
+  int32_t* seq_table;
+  uint8_t* parked;
+  size_t fixed_bytes;
+};
+AttnWs carve_attn_ws(const sale_params_t* p, bool sparse, void* base) {
+  const size_t tile_bytes = (size_t)p->batch * p->n_kv_heads * p->seq_len * kHeadDim * sizeof(uint16_t);
+  const size_t n_units = (size_t)p->batch * p->n_q_heads * (p->seq_len / kBlockQ);
+  AttnWs w = {};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { uint8_t* ptr = (uint8_t*)base + off; off += (bytes + 63) & ~(size_t)63; return ptr; };
+  w.kp = (u32x4*)take(tile_bytes);
+  w.vp = (u32x4*)take(tile_bytes);
+  if (sparse) {
+    w.order = (int32_t*)take(n_units * sizeof(int32_t));
+    w.slot_of = (int32_t*)take(n_units * sizeof(int32_t));
+    w.assign = (int32_t*)take(n_units * (kMaskWordsMax / 2) * sizeof(int32_t));
+    w.load = (LaneLoad*)take(kLaneLoadBytes);
+    w.slot_counter = (int*)take(sizeof(int));
   }
-  const size_t tile_elems = (size_t)g.n_kvh * g.seq * kHeadDim;
-  u32x4* kp = (u32x4*)ws;
-  u32x4* vp = (u32x4*)((uint16_t*)ws + tile_elems);
-  // workspace: K' | V' | parked O^T state (32 KB per row block) | parked max / sum (1 KB) | unit order (i32) |
-  // balanced issue tables (i32, room for 32 window launches)
+  if (p->flags & SALE_FLAG_ATTN_INT8_QK) w.ops8 = take(int8_operand_bytes(p));
+  if (p->flags & SALE_FLAG_ATTN_FP8_PV) w.ops_fp8 = take(fp8_operand_bytes(p));
+  if (p->n_seqs > 0) w.seq_table = (int32_t*)take(seq_table_bytes(p));
+  w.parked = (uint8_t*)base + off;
+  w.fixed_bytes = off;
+  return w;
+}
+}  // namespace
+
+size_t attn_fixed_bytes(const sale_params_t* p, bool sparse) { return carve_attn_ws(p, sparse, nullptr).fixed_bytes; }
+
+// o: bf16 output, or (o32 != nullptr) fp32 output instead.  mask == nullptr: dense causal attention
+// (independent of b_k).  ws_bytes >= attn_fixed_bytes (checked by the callers); what lies beyond holds parking slots.
+int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
+                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, size_t ws_bytes, hipStream_t st) {
+  Geo g = make_geo(p);
+  const AttnWs w = carve_attn_ws(p, mask != nullptr, ws);
+  if (ws_bytes < w.fixed_bytes) return SALE_ERR_WORKSPACE;
+  if (p->n_seqs > 0) {
+    const int rc = build_seq_table(p, w.seq_table, st);
+    if (rc != SALE_OK) return rc;
+    g.seq_start = w.seq_table;
+  }
+  u32x4 *kp = w.kp, *vp = w.vp;
   const size_t n_units = (size_t)g.n_qh * g.n_qb;
-  f32x4* st_o = (f32x4*)((uint16_t*)ws + 2 * tile_elems);
-  float* st_ml = (float*)(st_o + n_units * 2048);
-  int32_t* order = (int32_t*)(st_ml + n_units * 256);
-  int32_t* assign = order + n_units;
+  const size_t n_slots_z = mask ? (ws_bytes - w.fixed_bytes) / kParkedRowBytes : 0;
+  const int n_slots = (int)(n_slots_z < n_units ? n_slots_z : n_units);
+  f32x4* st_o = (f32x4*)w.parked;                               // [slot] 32 KB
+  float* st_ml = (float*)(w.parked + (size_t)n_slots * 2048 * 16);      // [slot] 1 KB
+  int32_t *order = w.order, *assign = w.assign;
   rearrange_kv_kernel<<<dim3((unsigned)(g.n_kvh * (g.seq / 64))), dim3(256), 0, st>>>(g.seq, (const uint16_t*)k, g.sk,
-                                                                                    (const uint16_t*)v, g.sv, kp, vp);
+                                                                                    (const uint16_t*)v, g.sv, kp, vp,
+                                                                                    w.slot_counter);
   if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   const bool qk8 = (p->flags & SALE_FLAG_ATTN_INT8_QK) != 0;
   const bool pv8 = (p->flags & SALE_FLAG_ATTN_FP8_PV) != 0;      // (validated: only with qk8 and 64-key blocks)
   Qk8 q8o = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   if (qk8) {
-    // the 8-bit operand copies follow the unit order, on the next 64-byte boundary
-    const uintptr_t end = (uintptr_t)(assign + n_units * (kMaskWordsMax / 2)) + 16 + kLaneLoadBytes;
-    const uintptr_t base8 = (end + 63) & ~(uintptr_t)63;
-    const Int8Operands w = carve_int8_operands(p, (void*)base8);
-    int rc = launch_int8_operands(p, q, k, w, true, st);
+    const Int8Operands w8i = carve_int8_operands(p, (void*)w.ops8);
+    int rc = launch_int8_operands(p, q, k, w8i, true, st);
     if (rc != SALE_OK) return rc;
-    q8o = {w.q8, (const u32x4*)w.k8, w.q_scale, w.k_scale, w.k_mean, nullptr, nullptr};
-    if (pv8) {      // then the FP8 copy of V (the 8-bit region's size is a multiple of 64 bytes)
-      const Fp8Operands w8 = carve_fp8_operands(p, (void*)(base8 + ((int8_operand_bytes(p) - 64 + 63) & ~(size_t)63)));
+    q8o = {w8i.q8, (const u32x4*)w8i.k8, w8i.q_scale, w8i.k_scale, w8i.k_mean, nullptr, nullptr};
+    if (pv8) {
+      const Fp8Operands w8 = carve_fp8_operands(p, (void*)w.ops_fp8);
       rc = launch_fp8_operands(p, v, w8, true, st);
       if (rc != SALE_OK) return rc;
       q8o.v8p = (const u32x4*)w8.v8;
@@ -1046,21 +1096,15 @@ int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const
   const uint16_t* qq = (const uint16_t*)q;
   const bf16x8 *kpp = (const bf16x8*)kp, *vpp = (const bf16x8*)vp;
   if (mask) {
-    if (g.bk == 32)
-      return qk8 ? launch_sparse_rows<true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
-                                                  st_o, st_ml, st)
-                 : launch_sparse_rows<true, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
-                                                   lse, st_o, st_ml, st);
-    if (pv8)
-      return launch_sparse_rows<false, true, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
-                                                   st_o, st_ml, st);
-    return qk8 ? launch_sparse_rows<false, true>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32, lse,
-                                                 st_o, st_ml, st)
-               : launch_sparse_rows<false, false>(g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, (uint16_t*)o, o32,
-                                                  lse, st_o, st_ml, st);
+#define SALE_SPARSE_ARGS g, qq, kpp, vpp, q8o, mask, row_counts, order, assign, w.load, w.slot_of, w.slot_counter, n_slots, \
+                         (uint16_t*)o, o32, lse, st_o, st_ml, st
+    if (g.bk == 32) return qk8 ? launch_sparse_rows<true, true>(SALE_SPARSE_ARGS) : launch_sparse_rows<true, false>(SALE_SPARSE_ARGS);
+    if (pv8) return launch_sparse_rows<false, true, true>(SALE_SPARSE_ARGS);
+    return qk8 ? launch_sparse_rows<false, true>(SALE_SPARSE_ARGS) : launch_sparse_rows<false, false>(SALE_SPARSE_ARGS);
+#undef SALE_SPARSE_ARGS
   }
   const int units = g.n_qb * g.group;
-  const RowFilter all = {nullptr, 0, 0, -1, 0, -1, 0, 0};
+  const RowFilter all = {nullptr, -1, 0, -1, 0, 0};
   const dim3 grid((unsigned)(((units + 3) / 4) * g.n_kvh));
   if (pv8)
     attn_rows_kernel<4, false, true, true><<<grid, dim3(256), 0, st>>>(g, qq, kpp, vpp, q8o, nullptr, nullptr, nullptr, (uint16_t*)o,
@@ -1084,9 +1128,10 @@ extern "C" int sale_sparse_attn(const sale_params_t* p, const void* q, const voi
   if (!p || !q || !k || !v || !block_mask || !o) return SALE_ERR_NULL_ARG;
   int rc = validate_common(p, kGeomPath);
   if (rc != SALE_OK) return rc;
-  const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN);
+  // (any size from SALE_WS_SPARSE_ATTN_MIN on: what lies beyond the fixed part holds parking slots)
+  const size_t need = sale_workspace_bytes(p, SALE_WS_SPARSE_ATTN_MIN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, nullptr, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, block_mask, row_counts, o, nullptr, lse, ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void* k, const void* v, void* o, float* lse,
@@ -1096,5 +1141,5 @@ extern "C" int sale_dense_attn(const sale_params_t* p, const void* q, const void
   if (rc != SALE_OK) return rc;
   const size_t need = sale_workspace_bytes(p, SALE_WS_DENSE_ATTN);
   if (!ws || ws_bytes < need || ((uintptr_t)ws & 15)) return SALE_ERR_WORKSPACE;
-  return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, nullptr, lse, ws, (hipStream_t)stream);
+  return launch_attn_rows(p, q, k, v, nullptr, nullptr, o, nullptr, lse, ws, ws_bytes, (hipStream_t)stream);
 }

@@ -106,7 +106,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
   if (rc != SALE_OK) return finish(rc);
   sale_params_t full = *p;      // O of Sec. 3.3 is full attention in full precision
   full.flags &= ~(SALE_FLAG_ATTN_INT8_QK | SALE_FLAG_ATTN_FP8_PV);
-  rc = launch_attn_rows(&full, q, k, v, nullptr, nullptr, nullptr, c.o_full, nullptr, c.ws_att, st);
+  rc = launch_attn_rows(&full, q, k, v, nullptr, nullptr, nullptr, c.o_full, nullptr, c.ws_att, c.att_bytes, st);
   if (rc != SALE_OK) return finish(rc);
 
   for (int round = 0; round <= max_halvings; ++round) {
@@ -114,7 +114,7 @@ extern "C" int sale_calibrate_tau(const sale_params_t* p, const void* q, const v
     rc = sale_select(p, q, k, c.q4, c.k4, c.qs, c.ks, c.tau, Hq, c.mask, c.counts, nullptr, nullptr, c.ws_sel, c.sel_bytes,
                      stream);
     if (rc != SALE_OK) return finish(rc);
-    rc = launch_attn_rows(p, q, k, v, c.mask, c.counts, nullptr, c.o_sale, nullptr, c.ws_att, st);
+    rc = launch_attn_rows(p, q, k, v, c.mask, c.counts, nullptr, c.o_sale, nullptr, c.ws_att, c.att_bytes, st);
     if (rc != SALE_OK) return finish(rc);
     l1_distance_kernel<<<dim3((unsigned)(B * Hq)), dim3(1024), 0, st>>>((const f32x4*)c.o_full, (const f32x4*)c.o_sale,
                                                                         N * kHeadDim / 4, c.err);

@@ -133,7 +133,10 @@ enum GeomClass { kGeomQuantize, kGeomPath };
 int validate_common(const sale_params_t* p, GeomClass cls);
 // attention launcher shared by the attention entry points and the calibration (attention.hip)
 int launch_attn_rows(const sale_params_t* p, const void* q, const void* k, const void* v, const uint64_t* mask,
-                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, hipStream_t st);
+                     const int32_t* row_counts, void* o, float* o32, float* lse, void* ws, size_t ws_bytes, hipStream_t st);
+// Bytes of an attention workspace without parking slots (sparse) / of the dense kernel's workspace.
+size_t attn_fixed_bytes(const sale_params_t* p, bool sparse);
+constexpr size_t kParkedRowBytes = 2048 * 16 + 256 * 4;      // fp32 O^T accumulators + running max / sum of one row block
 Geo make_geo(const sale_params_t* p);
 // Variable-length batches: bytes of the per-block sequence table at the end of a workspace (0 without one), and
 // the kernel launches that fill it from the host offsets.

@@ -31,6 +31,8 @@ WS_DENSE_ATTN = 3
 WS_CALIBRATE = 4
 WS_INT8_OPERANDS = 5
 WS_FP8_OPERANDS = 6
+WS_SPARSE_ATTN_MIN = 7
+PARKED_ROW_BYTES = 33792      # one parking slot of sparse_attn's workspace (see include/sale.h)
 
 
 class _Params(ctypes.Structure):

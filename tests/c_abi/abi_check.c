@@ -55,7 +55,8 @@ int main(void) {
   uint64_t* mask;
   int32_t* counts;
   const size_t sel_bytes = sale_workspace_bytes(&p, SALE_WS_SELECT), att_bytes = sale_workspace_bytes(&p, SALE_WS_SPARSE_ATTN);
-  CHECK(sel_bytes > 0 && att_bytes > 0 && att_bytes == sale_workspace_bytes(&p, SALE_WS_DENSE_ATTN));
+  CHECK(sel_bytes > 0 && att_bytes > 0 && att_bytes > sale_workspace_bytes(&p, SALE_WS_DENSE_ATTN));
+  CHECK(sale_workspace_bytes(&p, SALE_WS_SPARSE_ATTN_MIN) + (size_t)p.n_q_heads * (p.seq_len / 64) * SALE_PARKED_ROW_BYTES == att_bytes);
   HIP(hipMalloc(&q, nq_el * 2)); HIP(hipMalloc(&k, nkv_el * 2)); HIP(hipMalloc(&v, nkv_el * 2)); HIP(hipMalloc(&o, nq_el * 2));
   HIP(hipMalloc((void**)&q4, nq_el / 2)); HIP(hipMalloc((void**)&k4, nkv_el / 2));
   HIP(hipMalloc((void**)&qs, (size_t)HQ * NQ * 4)); HIP(hipMalloc((void**)&ks, (size_t)HKV * NQ * 4));

@@ -43,8 +43,15 @@ def test_status_strings(sale):
 def test_workspace_sizes(sale):
     p = sale.Params(1, 32, 8, 131072)
     assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4 + (32 + 8) * 131072 * 96
-    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == 2 * 8 * 131072 * 128 * 2 + 32 * 2048 * (33 * 4 + 32768 + 1024) + (128 << 10) + 16
-    assert sale.workspace_bytes(p, sale.WS_DENSE_ATTN) == sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)
+    kv = 2 * 8 * 131072 * 128 * 2                     # K', V' in operand order
+    units = 32 * 2048
+    fixed = kv + units * 4 * (1 + 1 + 32) + (128 << 10) + 64      # order, slot per row block, 32 window tables, head loads, counter
+    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN_MIN) == fixed
+    assert sale.workspace_bytes(p, sale.WS_SPARSE_ATTN) == fixed + units * sale.PARKED_ROW_BYTES
+    assert sale.PARKED_ROW_BYTES == 32768 + 1024
+    assert sale.workspace_bytes(p, sale.WS_DENSE_ATTN) == kv      # the dense kernel parks nothing and needs no tables
+    p8 = sale.Params(1, 32, 8, 131072, flags=sale.FLAG_ATTN_INT8_QK)
+    assert sale.workspace_bytes(p8, sale.WS_DENSE_ATTN) > kv + (32 + 8) * 131072 * 128
     assert sale.workspace_bytes(sale.Params(1, 32, 8, 100), sale.WS_SELECT) == 0   # invalid geometry
 
 

@@ -346,6 +346,36 @@ def test_many_kv_heads_beyond_the_balancing_table(sale):
         check_output(o_win[b, 0, rs].float().cpu().numpy(), ref, f"264 lanes b{b} i{i}")
 
 
+def test_fewer_parking_slots_than_long_rows_gives_the_same_bits(sale):
+    """The workspace beyond SALE_WS_SPARSE_ATTN_MIN holds the parking slots of the windowed sweep; a long row that
+    finds none is swept in one go.  With no slot, with slots for about half of the long rows and with one slot per
+    row block the outputs and lse are the same bit for bit (the block order of a row never changes)."""
+    w = LONG_ROWS_16K
+    q, k, v = inputs.make_inputs(w)
+    p = sale.Params(1, w.n_q_heads, w.n_kv_heads, w.seq_len)
+    qd, kd, vd = (t.unsqueeze(0).cuda() for t in (q, k, v))
+    tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
+    q4, k4, qs, ks = sale.quantize_qk(p, qd, kd)
+    mask, counts, _, _ = sale.select(p, qd, kd, q4, k4, qs, ks, tau)
+    n_long = int((counts > 192).sum())
+    assert n_long > 100
+    lo, full = sale.workspace_bytes(p, sale.WS_SPARSE_ATTN_MIN), sale.workspace_bytes(p, sale.WS_SPARSE_ATTN)
+    assert lo + p.n_q * w.n_q_heads * sale.PARKED_ROW_BYTES == full
+    outs = []
+    for nbytes in (full, lo + n_long * sale.PARKED_ROW_BYTES, lo + (n_long // 2) * sale.PARKED_ROW_BYTES, lo + 7, lo):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        o = torch.full_like(qd, float("nan"))
+        _, lse = sale.sparse_attn(p, qd, kd, vd, mask, counts, want_lse=True, out=o, ws=ws)
+        torch.cuda.synchronize()
+        outs.append((o.clone(), lse.clone()))
+        assert not torch.isnan(o).any()
+    for o, lse in outs[1:]:
+        assert torch.equal(o, outs[0][0]) and torch.equal(lse, outs[0][1])
+    with pytest.raises(sale.SaleError) as e:
+        sale.sparse_attn(p, qd, kd, vd, mask, counts, ws=torch.empty(lo - 1, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -4
+
+
 def _predict_balance_overflow(mask_bool, counts, n_qb, lanes, win_lo, win_hi, min_count):
     """The placement rule of the window tables, restated on the host from its description (a head whose work in
     the window exceeds the mean sheds n_in * (w - mean) / w units to the heads that lack work, in proportion to
