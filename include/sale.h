@@ -206,7 +206,7 @@ int sale_select(const sale_params_t* p, const void* q, const void* k,
  * until the process ends.  The call allocates and frees nothing.
  * - Geometries whose sale_workspace_bytes(p, SALE_WS_SELECT) exceeds
  *   SALE_SELECT_STATIC_MAX_BYTES return SALE_ERR_WORKSPACE and launch nothing
- *   (64 MiB covers 32 query / 8 KV heads up to 16384 tokens).
+ *   (64 MiB covers 32 query / 8 KV heads up to 65536 tokens).
  * - The device whose stream is passed must be the current device.  The first
  *   call on a device looks up that device's copy of the array.
  * - All calls on one GPU share that GPU's array: calls that overlap in time on

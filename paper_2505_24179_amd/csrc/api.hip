@@ -133,8 +133,8 @@ extern "C" size_t sale_workspace_bytes(const sale_params_t* p, int which_call) {
   const size_t rows = (size_t)p->batch * p->n_q_heads * p->seq_len;
   switch (which_call) {
     case SALE_WS_SELECT:
-      // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copies of Q~ and K~ (96 B per row)
-      return rows * sizeof(float) + (rows + (size_t)p->batch * p->n_kv_heads * p->seq_len) * 96 + seq_table_bytes(p);
+      // thr_r = ln(tau l~_r) + m~_r per query row, and the FP6 operand copy of K~ (96 B per row)
+      return rows * sizeof(float) + (size_t)p->batch * p->n_kv_heads * p->seq_len * 96 + seq_table_bytes(p);
     case SALE_WS_SPARSE_ATTN:
       // K and V copied once into MFMA fragment order, the order in which rows are issued, the tables (one per
       // window launch, at most 32) that balance them over the XCDs, the 8-bit operand copies of the quantized

@@ -142,8 +142,8 @@ __global__ __launch_bounds__(256) void stats_kernel(Geo g, const uint16_t* __res
 // v_mfma_f32_32x32x64_f8f6f4 with both operands in E2M3 and unit scales returns
 // the integer product EXACTLY in its fp32 accumulator (checked on hardware
 // against integer arithmetic, including all-(+-7) operands) at twice the int8
-// MFMA rate.  A pre-pass re-encodes the nibble codes once into MFMA operand
-// order ("X6"): per group of 32 rows 2 fragments ks (channels 64ks..); lane l of a
+// MFMA rate.  A pre-pass re-encodes the nibble codes of K~ once into MFMA operand
+// order ("X6"; Q~ is re-encoded by the wave that uses it): per group of 32 rows 2 fragments ks (channels 64ks..); lane l of a
 // fragment owns row l%32 of the group, channels 64ks + 32(l/32) + e, e = 0..31, as
 // 32 six-bit codes = 6 dwords, stored as
 //   [group][ks][lane] 16 bytes (dwords 0..3)  followed by  [group][ks][lane] 8 bytes (dwords 4..5).
@@ -174,7 +174,7 @@ __device__ __forceinline__ void pack_fp6(const u32x4 w, uint32_t out[6]) {
 }
 
 // One thread per (32-row group, fragment, lane) of a nibble-packed [rows][64-byte] matrix; a workgroup
-// handles two groups.  Q~ and K~ in one launch.
+// handles two groups.  (Two matrices in one launch; the second may be empty.)
 __global__ __launch_bounds__(256) void pack_fp6_kernel(const uint8_t* __restrict__ xa, uint8_t* __restrict__ ya,
                                                        long groups_a, const uint8_t* __restrict__ xb,
                                                        uint8_t* __restrict__ yb, long groups_b) {
@@ -243,7 +243,7 @@ __device__ __forceinline__ float lane_max(const f32x16 acc[MT][2], int nt) {
 // ordinary VGPRs instead of AGPRs that the max chain would have to copy out one by one.)
 template <int HPW, int MT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void select_kernel(
-    Geo g, const uint8_t* __restrict__ q6, const uint8_t* __restrict__ k6, const float* __restrict__ q_scale,
+    Geo g, const uint8_t* __restrict__ q4, const uint8_t* __restrict__ k6, const float* __restrict__ q_scale,
     const float* __restrict__ k_scale, const float* __restrict__ thr, uint64_t* __restrict__ mask,
     int32_t* __restrict__ row_counts) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave-uniform by construction
@@ -261,8 +261,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void s
   float th[HPW][2], cq[HPW];
 #pragma unroll
   for (int a = 0; a < HPW; ++a) {
-    load_x6(q6, ((size_t)(qh0 + a) * g.n_qb + i) * 2, lane, qf[a][0]);
-    load_x6(q6, ((size_t)(qh0 + a) * g.n_qb + i) * 2 + 1, lane, qf[a][1]);
+    // Q~ is used by this wave alone: its nibble codes are re-encoded here, once per row (K~, which every query
+    // block reads again, comes re-encoded from the pre-pass).  Lane (c, h) of fragment (row tile nt, ks) owns row
+    // 32 nt + c, channels 64 ks + 32 h ..: 16 bytes of the row.
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const uint8_t* row = q4 + ((size_t)(qh0 + a) * g.seq + i * 64 + 32 * nt + c) * 64 + 16 * (lane >> 5);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        uint32_t d[6];
+        pack_fp6(*(const u32x4*)(row + 32 * ks), d);
+#pragma unroll
+        for (int e = 0; e < 6; ++e) qf[a][nt][ks][e] = d[e];
+        qf[a][nt][ks][6] = 0; qf[a][nt][ks][7] = 0;
+      }
+    }
     th[a][0] = thr[(size_t)(qh0 + a) * g.seq + i * 64 + c];
     th[a][1] = thr[(size_t)(qh0 + a) * g.seq + i * 64 + 32 + c];
     cq[a] = q_scale[(size_t)(qh0 + a) * g.n_qb + i] * 0.08838834764831845f;   // s_q / sqrt(d)
@@ -439,7 +452,7 @@ using namespace sale;
 namespace {
 
 template <int MT>
-int launch_select(const Geo& g, bool est16, const void* q, const void* k, const uint8_t* q6, const uint8_t* k6,
+int launch_select(const Geo& g, bool est16, const void* q, const void* k, const uint8_t* q4, const uint8_t* k6,
                   const float* q_scale, const float* k_scale, const float* tau, int tau_len, const float* thr_c,
                   float* thr, uint64_t* block_mask, int32_t* row_counts, float* m_out, float* l_out, hipStream_t st) {
   const int tiles = (g.n_qb * g.group + 3) / 4;
@@ -451,14 +464,14 @@ int launch_select(const Geo& g, bool est16, const void* q, const void* k, const 
                                                                                 thr_c, block_mask, row_counts);
   } else if (MT == 2 && g.group % 4 == 0) {     // (with 32-key blocks two heads per wave are faster: 15.8 against 17.1 ms at 128K)
     const int t4 = (g.n_qb * (g.group / 4) + 3) / 4;
-    select_kernel<4, MT><<<dim3((unsigned)(t4 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr_c,
+    select_kernel<4, MT><<<dim3((unsigned)(t4 * g.n_kvh)), dim3(256), 0, st>>>(g, q4, k6, q_scale, k_scale, thr_c,
                                                                               block_mask, row_counts);
   } else if (g.group % 2 == 0) {
     const int t2 = (g.n_qb * (g.group / 2) + 3) / 4;
-    select_kernel<2, MT><<<dim3((unsigned)(t2 * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr_c,
+    select_kernel<2, MT><<<dim3((unsigned)(t2 * g.n_kvh)), dim3(256), 0, st>>>(g, q4, k6, q_scale, k_scale, thr_c,
                                                                               block_mask, row_counts);
   } else {
-    select_kernel<1, MT><<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, q6, k6, q_scale, k_scale, thr_c,
+    select_kernel<1, MT><<<dim3((unsigned)(tiles * g.n_kvh)), dim3(256), 0, st>>>(g, q4, k6, q_scale, k_scale, thr_c,
                                                                                  block_mask, row_counts);
   }
   return hipGetLastError() == hipSuccess ? SALE_OK : SALE_ERR_HIP;
@@ -490,22 +503,21 @@ int run_select(const sale_params_t* p, const void* q, const void* k, const uint8
   const bool est16 = (p->flags & SALE_FLAG_SELECT_16BIT) != 0;
   Geo g = make_geo(p);
   float* thr = (float*)ws;
-  uint8_t* q6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
-  uint8_t* k6 = q6 + (size_t)g.n_qh * (g.seq / 32) * kX6GroupBytes;
-  if (p->n_seqs > 0) {      // the per-block sequence table follows the operand copies
+  uint8_t* k6 = (uint8_t*)ws + (size_t)g.n_qh * g.seq * sizeof(float);
+  if (p->n_seqs > 0) {      // the per-block sequence table follows the operand copy
     int32_t* table = (int32_t*)(k6 + (size_t)g.n_kvh * (g.seq / 32) * kX6GroupBytes);
     const int rc = build_seq_table(p, table, st);
     if (rc != SALE_OK) return rc;
     g.seq_start = table;
   }
-  const long qgroups = (long)g.n_qh * (g.seq / 32), kgroups = (long)g.n_kvh * (g.seq / 32);
+  const long kgroups = (long)g.n_kvh * (g.seq / 32);
   if (!est16) {
-    pack_fp6_kernel<<<dim3((unsigned)((qgroups + kgroups + 1) / 2)), dim3(256), 0, st>>>(q4, q6, qgroups, k4, k6, kgroups);
+    pack_fp6_kernel<<<dim3((unsigned)((kgroups + 1) / 2)), dim3(256), 0, st>>>(k4, k6, kgroups, nullptr, nullptr, 0);
     if (hipGetLastError() != hipSuccess) return SALE_ERR_HIP;
   }
-  return g.bk == 64 ? launch_select<2>(g, est16, q, k, q6, k6, q_scale, k_scale, tau, tau_len, thr, thr, block_mask,
+  return g.bk == 64 ? launch_select<2>(g, est16, q, k, q4, k6, q_scale, k_scale, tau, tau_len, thr, thr, block_mask,
                                        row_counts, m_out, l_out, st)
-                    : launch_select<1>(g, est16, q, k, q6, k6, q_scale, k_scale, tau, tau_len, thr, thr, block_mask,
+                    : launch_select<1>(g, est16, q, k, q4, k6, q_scale, k_scale, tau, tau_len, thr, thr, block_mask,
                                        row_counts, m_out, l_out, st);
 }
 

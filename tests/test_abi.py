@@ -42,7 +42,7 @@ def test_status_strings(sale):
 
 def test_workspace_sizes(sale):
     p = sale.Params(1, 32, 8, 131072)
-    assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4 + (32 + 8) * 131072 * 96
+    assert sale.workspace_bytes(p, sale.WS_SELECT) == 32 * 131072 * 4 + 8 * 131072 * 96
     kv = 2 * 8 * 131072 * 128 * 2                     # K', V' in operand order
     units = 32 * 2048
     fixed = kv + units * 4 * (1 + 1 + 32) + (128 << 10) + 64      # order, slot per row block, 32 window tables, head loads, counter
@@ -153,7 +153,7 @@ def test_static_scratch_select_checks_before_touching_the_gpu(sale):
     import ctypes
     lib = sale.raw()
     f = ctypes.c_void_p(0x1000)        # never dereferenced
-    too_big = sale.Params(1, 32, 8, 32768)
+    too_big = sale.Params(1, 32, 8, 131072)
     assert sale.workspace_bytes(too_big, sale.WS_SELECT) > sale.SELECT_STATIC_MAX_BYTES
     assert lib.sale_select_static(ctypes.byref(too_big.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None) == -4
     fits = sale.Params(1, 32, 8, 16384)

@@ -78,7 +78,7 @@ def test_static_scratch_select_equals_workspace_select_twice_in_a_row(sale):
 def test_static_scratch_select_rejects_what_does_not_fit(sale):
     """A geometry whose scratch exceeds the static array is refused before anything is launched."""
     lib = sale.raw()
-    p = sale.Params(1, 32, 8, 32768)
+    p = sale.Params(1, 32, 8, 131072)
     assert sale.workspace_bytes(p, sale.WS_SELECT) > sale.SELECT_STATIC_MAX_BYTES
     f = ctypes.c_void_p(0x1000)        # never dereferenced
     assert lib.sale_select_static(ctypes.byref(p.c()), f, f, f, f, f, f, f, 1, f, f, None, None, None) == -4
