@@ -43,7 +43,7 @@ def _run(sale, p, q, k, v, o, tau, want_int8=False):
 
 
 @pytest.mark.parametrize("layout", ["bnhd", "padded"])
-@pytest.mark.parametrize("flags_name", ["bf16", "int8qk"])
+@pytest.mark.parametrize("flags_name", ["bf16", "int8qk", "fp8pv"])
 def test_strided_inputs_and_output_equal_the_contiguous_call(sale, layout, flags_name):
     w = inputs.scaled(inputs.LLAMA_32K, 2112, 4, 2, "strided-2k")       # 33 blocks: a ragged second mask word... of one word
     q, k, v = inputs.make_inputs(w)
@@ -53,7 +53,7 @@ def test_strided_inputs_and_output_equal_the_contiguous_call(sale, layout, flags
     qb = (q[None].float() * scale).bfloat16().cuda()
     kb = k[None].expand(B, -1, -1, -1).contiguous().cuda()
     vb = (v[None].float() * scale).bfloat16().cuda()
-    flags = sale.FLAG_ATTN_INT8_QK if flags_name == "int8qk" else 0
+    flags = {"bf16": 0, "int8qk": sale.FLAG_ATTN_INT8_QK, "fp8pv": sale.FLAG_ATTN_INT8_QK | sale.FLAG_ATTN_FP8_PV}[flags_name]
     p = sale.Params(B, w.n_q_heads, w.n_kv_heads, w.seq_len, flags=flags)
     tau = torch.tensor([w.tau], dtype=torch.float32, device="cuda")
     ref = _run(sale, p, qb, kb, vb, torch.empty_like(qb), tau)
