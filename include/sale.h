@@ -31,8 +31,8 @@
  * - Return value: SALE_OK (0) or a negative sale_status.  Arguments are checked
  *   before anything is launched; a failed check launches nothing.
  * - Supported geometry: head_dim = 128; block_q = 64; block_k = 64, or 32
- *   (the paper's shape, Sec. 4.1) for sale_quantize_qk, sale_select and
- *   sale_qk_int4_products; seq_len a multiple of 64 and at most 4096 key
+ *   (the paper's shape, Sec. 4.1) in every call (the dense kernel does not
+ *   depend on it); seq_len a multiple of 64 and at most 4096 key
  *   blocks; n_q_heads a multiple of n_kv_heads.  (sale_quantize_qk alone also
  *   accepts block_q = 32.)  Anything else returns SALE_ERR_UNSUPPORTED.
  *   A sequence whose length is not a multiple of 64 is passed zero-padded to
